@@ -1,0 +1,207 @@
+"""Pins for the oracle's number formats and rounding functions (CPU only).
+
+Each test compares the oracle with something other than itself: constants the paper prints
+(tests/golden/paper_constants.txt), a library float8 cast, exact rational arithmetic, or a
+closed form.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_constants():
+    out = {}
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, v = line.split(":")
+            out[k.strip()] = [float(t) for t in v.split()]
+    return out
+
+
+def all_bf16_positive_finite():
+    bits = np.arange(1, 0x7F80, dtype=np.uint32)            # every positive finite bf16
+    return (bits << np.uint32(16)).view(np.float32)
+
+
+# ---------------------------------------------------------------- E2M1 (Section 2 value set)
+
+def test_e2m1_value_set_is_the_papers(oracle):
+    want = read_constants()["e2m1_magnitudes"]
+    got = [oracle.e2m1_decode(c) for c in range(8)]
+    assert got == want
+    assert [oracle.e2m1_decode(c | 8) for c in range(8)] == [-w for w in want]
+    assert max(got) == read_constants()["e2m1_max"][0]
+    # the widest gap of the set is between 4 and 6 (Section 2)
+    gaps = np.diff(got)
+    assert gaps.argmax() == 6 and gaps[6] == 2.0
+
+
+def test_e2m1_rounding_ties_and_clipping(oracle):
+    # mid-points of neighbouring values go to the value with even mantissa bit (RNE)
+    ties = {0.25: 0.0, 0.75: 1.0, 1.25: 1.0, 1.75: 2.0, 2.5: 2.0, 3.5: 4.0, 5.0: 4.0}
+    for y, want in ties.items():
+        for s in (1.0, -1.0):
+            assert oracle.e2m1_decode(oracle.e2m1_round_mag(s * y)) == want
+        up = np.nextafter(np.float32(y), np.float32(np.inf))
+        dn = np.nextafter(np.float32(y), np.float32(0))
+        grid = read_constants()["e2m1_magnitudes"]
+        k = max(i for i, g in enumerate(grid) if g < y)
+        assert oracle.e2m1_round_mag(up) == k + 1
+        assert oracle.e2m1_round_mag(dn) == k
+    for y in (6.0, 6.5, 7.0, 100.0, 3e38, float("inf")):
+        assert oracle.e2m1_round_mag(y) == 7
+    assert oracle.e2m1_round_mag(5.0000005) == 7
+    assert oracle.e2m1_round_mag(0.0) == 0 and oracle.e2m1_round_mag(-0.0) == 0
+
+
+def test_e2m1_rounding_is_nearest_value(oracle):
+    rng = np.random.default_rng(3)
+    y = np.concatenate([rng.uniform(0, 8, 20000), rng.exponential(0.3, 20000)]).astype(np.float32)
+    grid = np.array(read_constants()["e2m1_magnitudes"])
+    d = np.abs(y.astype(np.float64)[:, None] - grid[None, :])
+    srt = np.sort(d, axis=1)
+    off_tie = srt[:, 0] < srt[:, 1]
+    want = d.argmin(axis=1)
+    got = np.array([oracle.e2m1_round_mag(v) for v in y])
+    assert off_tie.sum() > 39000
+    assert (got[off_tie] == want[off_tie]).all()
+
+
+# ---------------------------------------------------------------- E4M3 (OFP8, sign unused)
+
+def test_e4m3_table_against_library_float8(oracle):
+    codes = torch.arange(0, 0x7F, dtype=torch.uint8)
+    lib = codes.view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    got = np.array([oracle.scale_decode(oracle.SCALE_E4M3, c) for c in range(0x7F)], np.float32)
+    assert (got == lib).all()
+    assert math.isnan(oracle.scale_decode(oracle.SCALE_E4M3, 0x7F))
+    assert all(math.isnan(oracle.scale_decode(oracle.SCALE_E4M3, c)) for c in range(0x80, 0x100))
+    c = read_constants()
+    assert oracle.scale_eps(oracle.SCALE_E4M3) == 2.0 ** c["eps_e4m3_log2"][0]
+    assert oracle.scale_decode(oracle.SCALE_E4M3, 0x01) == 2.0 ** -9
+    assert oracle.scale_decode(oracle.SCALE_E4M3, oracle.scale_max_code(oracle.SCALE_E4M3)) == c["e4m3_max"][0]
+    assert oracle.scale_decode(oracle.SCALE_E4M3, 0x38) == 1.0
+    assert oracle.num_candidates(oracle.SCALE_E4M3) == 126
+    assert (np.diff(got) > 0).all()
+
+
+def test_e4m3_round_sf_against_library_cast(oracle):
+    """Round_SF of Eq. 2 = RNE cast to float8 (library routine), clipped to 448."""
+    x = all_bf16_positive_finite()
+    rng = np.random.default_rng(5)
+    extra = np.exp(rng.uniform(np.log(1e-5), np.log(600.0), 30000)).astype(np.float32)
+    # every mid-point between neighbouring codes, and its two fp32 neighbours
+    vals = np.array([oracle.scale_decode(1, c) for c in range(0x7F)], np.float64)
+    mids = ((vals[:-1] + vals[1:]) / 2).astype(np.float32)
+    assert (mids.astype(np.float64) == (vals[:-1] + vals[1:]) / 2).all()
+    near = np.concatenate([mids, np.nextafter(mids, np.float32(np.inf)),
+                           np.nextafter(mids, np.float32(0))])
+    r = np.concatenate([x, extra, near, np.float32([0.0, 448.0, 464.0, 480.0, 1e30])])
+    clipped = np.minimum(r, np.float32(448.0))
+    lib = torch.from_numpy(clipped).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.round_sf(oracle.SCALE_E4M3, v) for v in r], np.uint8)
+    assert (got == lib).all()
+    # tie at 2^-10 (half of the smallest value) goes to the even code 0
+    assert oracle.round_sf(1, 2.0 ** -10) == 0
+    assert oracle.round_sf(1, float(np.nextafter(np.float32(2.0 ** -10), np.float32(1)))) == 1
+
+
+# ---------------------------------------------------------------- UE5M3 (this build's reading)
+
+def test_ue5m3_table_structure(oracle):
+    """Parity with the format's own definition is unpinned (the paper gives no encoding);
+    this checks the stated reading: bias 15, subnormals m*2^-17, 0xFF NaN, max 1.75*2^16,
+    and that it is E4M3 shifted by 8 binades (same 3-bit mantissa, one more exponent bit)."""
+    f = oracle.SCALE_UE5M3
+    got = np.array([oracle.scale_decode(f, c) for c in range(0xFF)])
+    assert (np.diff(got) > 0).all() and got[0] == 0.0
+    assert oracle.scale_eps(f) == 2.0 ** -17
+    assert got[0xFE] == 1.75 * 2 ** 16
+    assert math.isnan(oracle.scale_decode(f, 0xFF))
+    assert oracle.num_candidates(f) == 254
+    assert oracle.scale_decode(f, 0x78) == 1.0
+    e4 = np.array([oracle.scale_decode(oracle.SCALE_E4M3, c) for c in range(0x7F)])
+    assert (got[:0x7F] * 2.0 ** 8 == e4).all()
+    # wider absolute range than E4M3 on both ends (Background / Section 3.2)
+    assert got[1] < e4[1] and got[0xFE] > e4[0x7E]
+
+
+def test_ue5m3_round_sf_is_rne_by_rational_arithmetic(oracle):
+    f = oracle.SCALE_UE5M3
+    vals = [Fraction(oracle.scale_decode(f, c)) for c in range(0xFF)]
+    rng = np.random.default_rng(11)
+    r = np.exp(rng.uniform(np.log(1e-7), np.log(3e5), 3000)).astype(np.float32)
+    mids = [float((vals[i] + vals[i + 1]) / 2) for i in range(0, 0xFE, 7)]
+    r = np.concatenate([r, np.float32(mids)])
+    for v in r:
+        fv = Fraction(float(v))
+        d = [abs(fv - t) for t in vals]
+        m = min(d)
+        winners = [c for c, dd in enumerate(d) if dd == m]
+        want = winners[0] if len(winners) == 1 else [c for c in winners if c % 2 == 0][0]
+        assert oracle.round_sf(f, float(v)) == want
+
+
+# ---------------------------------------------------------------- E8M0 / Eq. 1
+
+def test_e8m0_table(oracle):
+    f = oracle.SCALE_E8M0
+    assert oracle.scale_decode(f, 127) == 1.0
+    assert oracle.scale_decode(f, 126) == 0.5
+    assert oracle.scale_decode(f, 0) == 2.0 ** -127
+    assert oracle.scale_decode(f, 254) == 2.0 ** 127
+    assert math.isnan(oracle.scale_decode(f, 255))
+    assert oracle.num_candidates(f) == 255
+
+
+def test_eq1_closed_form_spot_values(oracle):
+    """Eq. 1: the largest power of two <= amax / M_max, M_max = 6 for E2M1."""
+    for amax, S in [(6.0, 1.0), (5.99, 0.5), (12.0, 2.0), (11.99, 1.0), (1.0, 0.125),
+                    (0.75, 0.125), (0.7499, 0.0625), (3.0, 0.5), (448.0, 64.0)]:
+        assert oracle.scale_decode(oracle.SCALE_E8M0, oracle.pow2_code(amax)) == S
+
+
+def test_eq1_floor_log2_on_all_bf16(oracle):
+    """floor(log2(amax/6)) in exact rational arithmetic for every positive finite bf16."""
+    x = all_bf16_positive_finite()
+    step = 7                                          # every 7th value + all exact 6*2^k
+    sample = list(x[::step]) + [np.float32(6.0 * 2.0 ** k) for k in range(-120, 120)]
+    for a in sample:
+        q = Fraction(float(a)) / 6
+        k = q.numerator.bit_length() - q.denominator.bit_length()
+        if Fraction(2) ** k > q:
+            k -= 1
+        assert Fraction(2) ** k <= q < Fraction(2) ** (k + 1)
+        want = min(max(k + 127, 0), 254)
+        assert oracle.pow2_code(float(a)) == want, float(a)
+    assert oracle.pow2_code(0.0) == 0
+
+
+def test_eq2_no_double_rounding(oracle):
+    """Rounding fl32(amax/M) equals rounding the exact quotient amax/M (Eq. 2 is stated in
+    real arithmetic; the oracle divides in fp32 first)."""
+    x = all_bf16_positive_finite()
+    x = x[(x > 1e-8) & (x < 1e7)][::3]
+    for fmt in (oracle.SCALE_E4M3, oracle.SCALE_UE5M3):
+        vals = [Fraction(oracle.scale_decode(fmt, c)) for c in range(oracle.scale_max_code(fmt) + 1)]
+        fl = np.array([float(v) for v in vals])
+        for M in (6.0, 4.0):
+            for a in x[::5]:
+                q = Fraction(float(a)) / Fraction(M)
+                i = int(np.searchsorted(fl, float(q)))
+                cands = [c for c in (i - 1, i, i + 1) if 0 <= c < len(vals)]
+                d = {c: abs(q - vals[c]) for c in cands}
+                m = min(d.values())
+                win = [c for c in cands if d[c] == m]
+                want = win[0] if len(win) == 1 else [c for c in win if c % 2 == 0][0]
+                got = oracle.round_sf(fmt, float(np.float32(a) / np.float32(M)))
+                assert got == want

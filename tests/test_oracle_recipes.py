@@ -1,0 +1,343 @@
+"""Pins for the oracle's recipes (CPU only): worked blocks derived by hand, exhaustive
+enumeration in exact integer arithmetic, the invariants the method implies, and the
+qualitative findings of the paper's numerical study."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_08565_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+FMT = {"e8m0": 0, "e4m3": 1, "ue5m3": 2}
+REC = {"absmax": 0, "absmax_pz": 1, "4over6": 2, "4over6_pz": 3, "brute": 4}
+E2M1 = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]          # Section 2 value set
+
+
+def worked_blocks():
+    rows = []
+    with open(os.path.join(GOLDEN, "worked_blocks.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            head, vals, scale, codes, sse = [t.strip() for t in line.split("|")]
+            fmt, rec = head.split()
+            rows.append((fmt, rec, [float(v) for v in vals.split()], int(scale, 16),
+                         [int(c, 16) for c in codes.split()], float(sse)))
+    return rows
+
+
+@pytest.mark.parametrize("case", worked_blocks(), ids=lambda c: f"{c[0]}-{c[1]}-{c[2][0]}")
+def test_worked_blocks(oracle, case):
+    fmt, rec, vals, scale, codes, sse = case
+    x = np.array([vals], np.float32)
+    c, s, e = oracle.quantize(x, 4, FMT[fmt], REC[rec])
+    assert s[0, 0] == scale
+    assert list(c[0]) == codes
+    assert e[0, 0] == np.float32(sse)
+    # the same block stored as bf16 (all values are bf16-representable) gives the same result
+    c2, s2, e2 = oracle.quantize(W.f32_to_bf16_bits(x), 4, FMT[fmt], REC[rec])
+    assert (c2 == c).all() and (s2 == s).all() and (e2 == e).all()
+
+
+# ---------------------------------------------------------------- exhaustive, exact integers
+
+def e4m3_values_from_library():
+    codes = torch.arange(0, 0x7F, dtype=torch.uint8)
+    return [float(v) for v in codes.view(torch.float8_e4m3fn).to(torch.float64)]
+
+
+def exact_block_search(vals, scale_values, unit_log2):
+    """Try every positive scale, nearest E2M1 value by distance, exact integer SSE.
+    All numbers are integer multiples of 2^unit_log2.  Returns (best code, SSE int, mags)."""
+    U = 2 ** (-unit_log2)
+    vi = [int(round(v * U)) for v in vals]
+    assert all(abs(a / U - v) == 0 for a, v in zip(vi, vals))
+    best = None
+    for code, S in enumerate(scale_values):
+        if not S > 0:
+            continue
+        gi = [int(round(g * S * U)) for g in E2M1]
+        assert all(g / U == t * S for g, t in zip(gi, E2M1))
+        sse, mags = 0, []
+        for a in vi:
+            aa = abs(a)
+            d = [abs(aa - g) for g in gi]
+            m = min(d)
+            win = [k for k in range(8) if d[k] == m]
+            k = win[0] if len(win) == 1 else [w for w in win if w % 2 == 0][0]
+            mags.append(k)
+            sse += m * m
+        if best is None or sse < best[1]:
+            best = (code, sse, mags)
+    return best
+
+
+LATTICE = [0.0, 2.0 ** -12, 2.0 ** -10, 3 * 2.0 ** -11, 2.0 ** -9, 5 * 2.0 ** -10, 2.0 ** -7,
+           0.01171875, 0.0234375, 0.05859375, 0.09375, 0.15625, 0.3125, 0.4375, 0.5625, 0.8125,
+           1.0, 1.25, 1.75, 2.5, 3.0, 3.5, 5.0, 6.0, 7.0]
+
+
+def test_brute_force_exhaustive_pairs_e4m3(oracle):
+    """Block size 2, every ordered pair of a signed lattice of bf16 values: the oracle's
+    exact-mode brute force equals an independent search in integer arithmetic, and the
+    pinned fp32 selection reaches the same minimum up to rounding."""
+    svals = e4m3_values_from_library()
+    signed = sorted(set(LATTICE + [-v for v in LATTICE]))
+    pairs = np.array([[a, b] for a in signed for b in signed], np.float32)
+    cE, sE, _, exE = oracle.quantize(pairs, 2, oracle.SCALE_E4M3, oracle.BRUTE,
+                                     sel_mode=oracle.SEL_EXACT, want_exact=True)
+    cP, sP, sseP, exP = oracle.quantize(pairs, 2, oracle.SCALE_E4M3, oracle.BRUTE, want_exact=True)
+    unit = -40
+    for i, (a, b) in enumerate(pairs):
+        code, sse_int, mags = exact_block_search([float(a), float(b)], svals, unit)
+        assert sE[i, 0] == code, (a, b)
+        assert exE[i, 0] == sse_int * 2.0 ** (2 * unit)
+        got = [cE[i, 0] & 7, (cE[i, 0] >> 4) & 7]
+        assert got == mags
+        signs = [(cE[i, 0] >> 3) & 1, (cE[i, 0] >> 7) & 1]
+        assert signs == [int(np.signbit(a)), int(np.signbit(b))]
+        # pinned selection: same minimum within fp32 rounding of a two-term sum
+        assert exP[i, 0] <= exE[i, 0] * (1 + 1e-6) + 1e-300
+        assert abs(float(sseP[i, 0]) - exP[i, 0]) <= 2e-7 * exP[i, 0]
+
+
+def test_brute_force_exhaustive_pairs_ue5m3(oracle):
+    svals = [oracle.scale_decode(oracle.SCALE_UE5M3, c) for c in range(0xFF)]
+    lat = LATTICE[::2] + [300.0, 4096.0]
+    signed = sorted(set(lat + [-v for v in lat]))
+    pairs = np.array([[a, b] for a in signed for b in signed], np.float32)
+    cE, sE, _, exE = oracle.quantize(pairs, 2, oracle.SCALE_UE5M3, oracle.BRUTE,
+                                     sel_mode=oracle.SEL_EXACT, want_exact=True)
+    unit = -40
+    for i, (a, b) in enumerate(pairs):
+        code, sse_int, mags = exact_block_search([float(a), float(b)], svals, unit)
+        assert sE[i, 0] == code, (a, b)
+        assert [cE[i, 0] & 7, (cE[i, 0] >> 4) & 7] == mags
+        assert exE[i, 0] == pytest.approx(sse_int * 2.0 ** (2 * unit), rel=1e-15)
+
+
+def test_streaming_recipes_against_exact_integers(oracle):
+    """abs-max / prevent-zero / 4-over-6 on blocks of 4 from the lattice: the scale is the
+    E4M3 value nearest to amax/M (ties to even, exact rationals), the codes are the nearest
+    E2M1 values, and 4-over-6 keeps the better of the two."""
+    from fractions import Fraction
+    svals = e4m3_values_from_library()
+    rng = np.random.default_rng(17)
+    lat = np.array(sorted(set(LATTICE + [-v for v in LATTICE])), np.float32)
+    blocks = lat[rng.integers(0, len(lat), size=(400, 4))]
+
+    def nearest_scale(q):
+        d = [abs(q - Fraction(s)) for s in svals]
+        m = min(d)
+        win = [c for c in range(len(svals)) if d[c] == m]
+        return win[0] if len(win) == 1 else [c for c in win if c % 2 == 0][0]
+
+    def sse_under(vals, S):
+        if S == 0:
+            return sum(Fraction(float(v)) ** 2 for v in vals), [0] * len(vals)
+        tot, mags = Fraction(0), []
+        for v in vals:
+            a = abs(Fraction(float(v)))
+            d = [abs(a - Fraction(g) * Fraction(S)) for g in E2M1]
+            m = min(d)
+            win = [k for k in range(8) if d[k] == m]
+            k = win[0] if len(win) == 1 else [w for w in win if w % 2 == 0][0]
+            mags.append(k)
+            tot += m * m
+        return tot, mags
+
+    out = {r: oracle.quantize(blocks, 4, oracle.SCALE_E4M3, r, sel_mode=oracle.SEL_EXACT,
+                              want_exact=True) for r in range(4)}
+    for i, vals in enumerate(blocks):
+        amax = max(abs(Fraction(float(v))) for v in vals)
+        c6, c4 = nearest_scale(amax / 6), nearest_scale(amax / 4)
+        for pz, (ra, r46) in enumerate([(0, 2), (1, 3)]):
+            k6, k4 = (max(c6, 1), max(c4, 1)) if pz else (c6, c4)
+            s6, m6 = sse_under(vals, svals[k6])
+            s4, m4 = sse_under(vals, svals[k4])
+            assert out[ra][1][i, 0] == k6
+            assert [out[ra][0][i, j // 2] >> (4 * (j % 2)) & 7 for j in range(4)] == m6
+            assert out[ra][3][i, 0] == pytest.approx(float(s6), rel=1e-15, abs=0)
+            want_code, want_m = (k4, m4) if s4 < s6 else (k6, m6)
+            assert out[r46][1][i, 0] == want_code
+            assert [out[r46][0][i, j // 2] >> (4 * (j % 2)) & 7 for j in range(4)] == want_m
+
+
+# ---------------------------------------------------------------- invariants
+
+def _datasets():
+    w = W.student_t_weights(64, 512, seed=21)
+    a = W.outlier_activations(64, 512, seed=22)
+    n = W.normal_f32(64, 512, seed=23, sigma=0.004)
+    return [("weights", w, 1.0), ("acts", a, None), ("small-normal", n, 1.0)]
+
+
+@pytest.mark.parametrize("block", [2, 4, 8, 16, 32, 64, 128])
+def test_sse_chain_absmax_4over6_brute(oracle, block):
+    """SSE_absmax >= SSE_4over6 >= SSE_brute for every block, exactly (same arithmetic; every
+    candidate of the cheaper recipe is a brute-force candidate or the zero scale, which no
+    positive scale loses to)."""
+    for name, x, T in _datasets():
+        if T is None:
+            T = oracle.tensor_scale(oracle.tensor_absmax(x), oracle.SCALE_E4M3)
+        for fmt in (oracle.SCALE_E4M3, oracle.SCALE_UE5M3):
+            r = {k: oracle.quantize(x, block, fmt, k, tensor_scale=T)[2] for k in range(5)}
+            assert (r[0] >= r[2]).all(), name
+            assert (r[1] >= r[3]).all(), name
+            assert (r[2] >= r[4]).all() and (r[3] >= r[4]).all(), name
+            assert (r[0] >= r[1]).all(), name                  # the clamp never hurts
+            assert (r[2] >= r[3]).all() or fmt == oracle.SCALE_E4M3
+
+
+def test_prevent_zero_only_changes_zero_scale_blocks(oracle):
+    x = W.normal_f32(256, 64, seed=31, sigma=0.003)
+    c0, s0, e0 = oracle.quantize(x, 8, oracle.SCALE_E4M3, oracle.ABSMAX)
+    c1, s1, e1 = oracle.quantize(x, 8, oracle.SCALE_E4M3, oracle.ABSMAX_PZ)
+    z = s0 == 0
+    assert z.any() and (~z).any()
+    assert (s1[z] == 1).all() and (s1[~z] == s0[~z]).all()
+    assert (e1[~z] == e0[~z]).all() and (e1[z] <= e0[z]).all()
+    # a zero scale dequantises the whole block to zero: SSE = sum of squares
+    xb = x.reshape(-1, 8).astype(np.float64)
+    assert np.allclose(e0.reshape(-1)[z.reshape(-1)], (xb[z.reshape(-1)] ** 2).sum(1), rtol=1e-6)
+    assert (c0.reshape(-1, 4)[z.reshape(-1)] & 0x77 == 0).all()
+
+
+def test_brute_force_nesting(oracle):
+    """Optimal SSE of a block of 2b is at least the sum of the optimal SSEs of its halves
+    (each half may reuse the parent's scale), so the optimal MSE cannot decrease with block
+    size -- the monotonicity the numerical study reports for brute force."""
+    for name, x, T in _datasets():
+        if T is None:
+            T = oracle.tensor_scale(oracle.tensor_absmax(x), oracle.SCALE_E4M3)
+        prev = None
+        for block in (2, 4, 8, 16, 32, 64):
+            ex = oracle.quantize(x, block, oracle.SCALE_E4M3, oracle.BRUTE, tensor_scale=T,
+                                 sel_mode=oracle.SEL_EXACT, want_exact=True)[3]
+            if prev is not None:
+                halves = prev.reshape(prev.shape[0], -1, 2).sum(-1)
+                assert (ex >= halves * (1 - 1e-12)).all(), (name, block)
+            prev = ex
+
+
+def test_pinned_selection_differs_from_exact_only_on_near_ties(oracle):
+    x = W.student_t_weights(128, 1024, seed=41)
+    for rec in (oracle.FOUR_OVER_SIX, oracle.BRUTE):
+        for block in (4, 16, 64):
+            _, sP, _, exP = oracle.quantize(x, block, oracle.SCALE_E4M3, rec, want_exact=True)
+            _, sE, _, exE = oracle.quantize(x, block, oracle.SCALE_E4M3, rec,
+                                            sel_mode=oracle.SEL_EXACT, want_exact=True)
+            diff = sP != sE
+            assert diff.mean() < 0.01
+            assert (exP >= exE).all()
+            assert (exP[diff] <= exE[diff] * (1 + 1e-6)).all()
+
+
+def test_sse_is_the_dequantisation_error(oracle):
+    """sse_out equals sum (v - dequant)^2 recomputed from the emitted codes and scales."""
+    x = W.student_t_weights(32, 256, seed=51)
+    xf = W.bf16_bits_to_f32(x).astype(np.float64)
+    for fmt in (0, 1, 2):
+        for rec in ((0,) if fmt == 0 else (0, 1, 2, 3, 4)):
+            for block in (2, 16, 128):
+                c, s, e = oracle.quantize(x, block, fmt, rec)
+                xh = oracle.dequantize(c, s, block, fmt).astype(np.float64)
+                want = ((xf - xh) ** 2).reshape(32, -1, block).sum(-1)
+                assert np.allclose(e, want, rtol=2e-6, atol=0)
+
+
+def test_dequantize_definition(oracle):
+    """x^ = (q * S) * T from the decode tables the other pins fix; bf16 output rounds RNE."""
+    rng = np.random.default_rng(61)
+    codes = rng.integers(0, 256, size=(8, 32), dtype=np.uint8)
+    scales = rng.integers(1, 0x7F, size=(8, 64 // 4), dtype=np.uint8)
+    T = np.float32(0.0731)
+    out = oracle.dequantize(codes, scales, 4, oracle.SCALE_E4M3, tensor_scale=T)
+    lo, hi = codes & 0xF, codes >> 4
+    nib = np.stack([lo, hi], -1).reshape(8, 64)
+    q = np.array(E2M1)[nib & 7] * np.where(nib & 8, -1.0, 1.0)
+    sv = np.array(e4m3_values_from_library())[scales].repeat(4, axis=1)
+    want = (np.float32(q * sv) * T).astype(np.float32)
+    assert (out == want).all()
+    out16 = oracle.dequantize(codes, scales, 4, oracle.SCALE_E4M3, tensor_scale=T,
+                              out_dtype=oracle.DT_BF16)
+    lib = torch.from_numpy(want).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (out16 == lib).all()
+
+
+def test_hierarchical_scale(oracle):
+    """Per-tensor scale maps the tensor abs-max onto 6 * 448 (E4M3); with it the largest
+    block's M=6 scale is exactly the largest E4M3 value and nothing clips."""
+    x = W.outlier_activations(64, 1024, seed=71)
+    A = oracle.tensor_absmax(x)
+    assert A == float(np.abs(W.bf16_bits_to_f32(x)).max())
+    T = oracle.tensor_scale(A, oracle.SCALE_E4M3)
+    assert T == float(np.float32(A) / np.float32(2688.0))
+    assert oracle.tensor_scale(0.0, oracle.SCALE_E4M3) == 1.0
+    c, s, e = oracle.quantize(x, 16, oracle.SCALE_E4M3, oracle.ABSMAX, tensor_scale=T)
+    assert s.max() == 0x7E
+    # adjusted inputs are the fp32 quotient v / T
+    v = (W.bf16_bits_to_f32(x) / np.float32(T)).astype(np.float32)
+    c2, s2, e2 = oracle.quantize(v, 16, oracle.SCALE_E4M3, oracle.ABSMAX)
+    assert (c2 == c).all() and (s2 == s).all() and (e2 == e).all()
+    # without the tensor scale the outlier blocks saturate the E4M3 range less gracefully:
+    # MSE in the original domain is not worse with H on this tensor
+    e_noH = oracle.quantize(x, 16, oracle.SCALE_E4M3, oracle.ABSMAX)[2]
+    assert oracle.tensor_mse(e, x.size, T) <= oracle.tensor_mse(e_noH, x.size) * 1.05
+
+
+def test_tree_sum_order(oracle):
+    """The pinned SSE is the balanced binary tree over fp32 squares, in index order."""
+    rng = np.random.default_rng(81)
+    for b in (2, 4, 8, 16, 32, 64, 128):
+        v = (rng.standard_normal(b) * 10 ** rng.uniform(-3, 1, b)).astype(np.float32)
+        code = 0x30
+        c4, sp, se = oracle.block_sse(v, oracle.SCALE_E4M3, code)
+        S = np.float32(0.5)
+        q = np.array([np.float32(E2M1[c & 7]) * (-1 if c & 8 else 1) for c in c4], np.float32)
+        e = (v - q * S).astype(np.float32)
+        s = (e * e).astype(np.float32)
+        while len(s) > 1:
+            s = (s[0::2] + s[1::2]).astype(np.float32)
+        assert sp == s[0]
+        assert se == pytest.approx(float((e.astype(np.float64) ** 2).sum()), rel=1e-12)
+
+
+# ---------------------------------------------------------------- numerical study (Section 3.1)
+
+def test_numerical_study_regions(oracle):
+    """Qualitative findings of the MSE-vs-sigma figure on N(0, sigma^2) blocks."""
+    def mse(sigma, block, rec):
+        x = W.normal_blocks_f32(sigma, 1500, 32, seed=91).reshape(-1, block)
+        return oracle.tensor_mse(oracle.quantize(x, block, oracle.SCALE_E4M3, rec)[2], x.size) / sigma ** 2
+
+    # Region A: abs-max scale underflows to zero -> relative MSE ~ 1; prevent-zero removes it;
+    # 4-over-6 alone keeps the bump; brute force picks what prevent-zero picks.
+    for b in (4, 8, 16, 32):
+        assert mse(0.001, b, 0) > 0.9
+        assert mse(0.001, b, 2) > 0.9
+        assert mse(0.001, b, 1) < 0.12
+        assert mse(0.001, b, 4) == pytest.approx(mse(0.001, b, 1), rel=1e-3)
+    # Region B: with prevent-zero, smaller blocks are worse (the paradox); 4-over-6 resolves it
+    assert mse(0.008, 4, 1) > mse(0.008, 16, 1) > mse(0.008, 32, 1)
+    assert mse(0.008, 4, 3) < mse(0.008, 16, 3) < mse(0.008, 32, 3)
+    # Region C: no inversion; 4-over-6 and brute force clearly better at small blocks
+    assert mse(0.03, 4, 0) < mse(0.03, 32, 0)
+    assert mse(0.03, 4, 2) < 0.7 * mse(0.03, 4, 0)
+    # brute force: monotone in block size at every sigma
+    for sigma in (0.0005, 0.001, 0.004, 0.008, 0.02, 0.05):
+        m = [mse(sigma, b, 4) for b in (4, 8, 16, 32)]
+        assert all(hi >= lo * (1 - 1e-6) for lo, hi in zip(m, m[1:]))   # fp32 SSE rounding
+
+
+def test_4over6_moves_mass_from_bin_6_to_bin_4(oracle):
+    x = W.normal_blocks_f32(0.03, 4000, 4, seed=93)
+    def hist(rec):
+        c = oracle.quantize(x, 4, oracle.SCALE_E4M3, rec)[0]
+        mags = np.concatenate([(c & 7).ravel(), ((c >> 4) & 7).ravel()])
+        return np.bincount(mags, minlength=8)
+    h0, h2 = hist(0), hist(2)
+    assert h2[7] < h0[7] and h2[6] > h0[6]
