@@ -1,0 +1,143 @@
+/*
+ * mxq.h -- C ABI of libmxq: block-wise microscaled FP4 (E2M1) quantise / de-quantise with
+ * per-block scale selection, as hand-written HIP kernels for gfx950 (AMD Instinct MI355X).
+ *
+ * The operations follow "Finer is Better (with the Right Scaling)", Section 2
+ * ("Experimental Setup"): Eq. 1 (power-of-two scale), Eq. 2 (abs-max scale rounded to the
+ * scale format), Eq. 3 (prevent-zero clamp), Eq. 4 (4-over-6), the hierarchical-scaling
+ * paragraph and the brute-force paragraph that close that section.
+ *
+ * Conventions common to every entry point
+ *   - Every pointer named "device" is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or synchronises: work is enqueued on `stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and the call returns at once.
+ *   - Tensors are row-major `rows x cols`, contiguous.  A block is `block` consecutive
+ *     elements of one row; `cols % block == 0`; block is one of 2,4,8,16,32,64,128.
+ *   - Every function that can fail returns an mxq_status (0 = success).  Arguments are
+ *     validated on the host before anything is launched; the library never aborts, throws
+ *     or prints.  Inputs are assumed finite: NaN/Inf elements give unspecified codes, never
+ *     a fault.
+ *   - Outputs are overwritten in full; they must not alias the input.
+ *   - Calls are re-entrant; there is no global mutable state.
+ */
+#ifndef MXQ_H
+#define MXQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MXQ_API __attribute__((visibility("default")))
+
+typedef enum {
+    MXQ_OK = 0,
+    MXQ_ERR_INVALID_ARG = -1,   /* NULL pointer, bad shape, unknown enum, bad tensor_scale  */
+    MXQ_ERR_UNSUPPORTED = -2,   /* well-formed request outside what the paper defines       */
+    MXQ_ERR_ALIGNMENT = -3,     /* a pointer is not aligned as stated below                 */
+    MXQ_ERR_HIP = -4            /* the HIP runtime reported an error at launch              */
+} mxq_status;
+
+/* Element format. E2M1 (OCP FP4): magnitudes {0, .5, 1, 1.5, 2, 3, 4, 6} (Section 2).
+ * A 4-bit code is sign<<3 | magnitude index. */
+typedef enum { MXQ_ELEM_E2M1 = 0 } mxq_elem_fmt;
+
+/* Scale format: one byte per block.
+ *   E8M0   power of two, value 2^(byte-127), chosen by the floor rule of Eq. 1.
+ *   E4M3   OFP8 E4M3 with the sign bit unused (Background): bias 7, subnormals m*2^-9
+ *          (eps = 2^-9, stated under Eq. 3), largest value 0x7E = 448, 0x7F = NaN (never
+ *          written).
+ *   UE5M3  unsigned, 5 exponent + 3 mantissa bits (Background, Section 3.2).  The paper
+ *          gives no encoding; this library uses bias 15, subnormals m*2^-17, largest value
+ *          0xFE = 1.75*2^16, 0xFF = NaN (never written). */
+typedef enum { MXQ_SCALE_E8M0 = 0, MXQ_SCALE_E4M3 = 1, MXQ_SCALE_UE5M3 = 2 } mxq_scale_fmt;
+
+/* Scale-selection recipe.
+ *   ABSMAX     S = Round_SF(amax / 6), round to nearest even, clipped to the largest finite
+ *              value (Eq. 2); for E8M0 the floor rule S = 2^floor(log2(amax/6)) (Eq. 1).
+ *   ABSMAX_PZ  S = max(S_absmax, eps_SF) (Eq. 3).  No effect for E8M0.
+ *   4OVER6     S_absmax(6) or S_absmax(4), whichever has the lower block SSE; M = 6 on a
+ *              tie (Eq. 4).
+ *   4OVER6_PZ  both candidates clamped by Eq. 3 first (Fig. 1(d) of the paper).
+ *   BRUTE      every finite, strictly positive scale code is tried; the lowest code of
+ *              minimal SSE is kept (brute-force paragraph, Section 2).
+ * 4OVER6*, BRUTE with E8M0 return MXQ_ERR_UNSUPPORTED. */
+typedef enum {
+    MXQ_RECIPE_ABSMAX = 0,
+    MXQ_RECIPE_ABSMAX_PZ = 1,
+    MXQ_RECIPE_4OVER6 = 2,
+    MXQ_RECIPE_4OVER6_PZ = 3,
+    MXQ_RECIPE_BRUTE = 4
+} mxq_recipe;
+
+typedef enum { MXQ_DT_BF16 = 0, MXQ_DT_F32 = 1 } mxq_dtype;
+
+/*
+ * mxq_quantize -- quantise one tensor (Section 2, Eq. 1-4).
+ *
+ * Per block: v_i = x_i / tensor_scale (IEEE fp32 division; skipped when tensor_scale == 1),
+ * amax = max |v_i|, scale S by `recipe`, q_i = E2M1 value nearest to v_i / S (ties to the
+ * even code, |v_i / S| > 5 gives 6; S == 0 gives magnitude 0), e_i = v_i - q_i * S,
+ * SSE = sum e_i^2 in fp32 (squares rounded separately, summed by the balanced binary tree in
+ * index order).  The sign bit of a code is the sign bit of x_i, also for zero magnitudes.
+ *
+ *   x            device, rows*cols elements of x_dtype, 16-byte aligned
+ *   tensor_scale the per-tensor scale T of hierarchical scaling, finite and > 0;
+ *                1.0f = no hierarchical scaling
+ *   codes_out    device, rows*cols/2 bytes, 4-byte aligned; byte j = code of element 2j in
+ *                bits 3:0, of element 2j+1 in bits 7:4
+ *   scales_out   device, rows*cols/block bytes, 4-byte aligned, row-major
+ *   sse_out      device, rows*cols/block floats, 16-byte aligned, row-major (SSE of the
+ *                selected scale, in the domain of v); NULL to skip
+ *   stream       hipStream_t, NULL = default stream
+ *
+ * rows*cols == 0 is a valid no-op.  Errors: INVALID_ARG (NULL x/codes_out/scales_out,
+ * negative size, bad block, cols % block != 0, unknown enum, tensor_scale not finite or
+ * <= 0), UNSUPPORTED (see mxq_recipe), ALIGNMENT, HIP.
+ */
+MXQ_API int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
+                 int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
+                 uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                 int x_dtype, void* stream);
+
+/*
+ * mxq_dequantize -- x^_i = (q_i * S) * tensor_scale, rounded to nearest even into out_dtype
+ * ("de-quantization simply multiplies by S", Section 2).
+ *
+ *   codes, scales  device, layouts as written by mxq_quantize, 4-byte aligned
+ *   x_out          device, rows*cols elements of out_dtype, 16-byte aligned
+ * A scale byte that is not a finite value of scale_fmt de-quantises to NaN.
+ */
+MXQ_API int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
+                   int64_t rows, int64_t cols, int block,
+                   int elem_fmt, int scale_fmt, float tensor_scale,
+                   void* x_out, int out_dtype, void* stream);
+
+/*
+ * mxq_tensor_absmax -- first stage of hierarchical scaling (Section 2): max |x_i| over the
+ * whole tensor, written as one float to absmax_out (device, 4-byte aligned).  x 16-byte
+ * aligned.  An empty tensor writes 0.
+ */
+MXQ_API int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                      float* absmax_out, void* stream);
+
+/* Host helper: the per-tensor scale that maps the tensor abs-max onto (largest element
+ * value) x (largest scale value): absmax / (6 * SF_max), e.g. absmax / 2688 for E4M3; 1 for
+ * an all-zero tensor or a format whose range makes the quotient vanish.  NaN on a bad enum. */
+MXQ_API float mxq_tensor_scale_from_absmax(float absmax, int elem_fmt, int scale_fmt);
+
+/* Host helper: value of a scale byte; NaN for a code that is not a finite number. */
+MXQ_API float mxq_scale_decode(int scale_fmt, uint8_t code);
+
+/* Host helper: number of candidates BRUTE tries (finite positive codes): 126 for E4M3,
+ * 254 for UE5M3, 255 for E8M0 (not searched); -1 on a bad enum. */
+MXQ_API int mxq_num_candidates(int scale_fmt);
+
+/* Host helper: static, human-readable name of a status code. */
+MXQ_API const char* mxq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MXQ_H */

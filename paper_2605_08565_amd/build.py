@@ -1,0 +1,32 @@
+"""Builds libmxq.so (hand-written HIP kernels for gfx950 + the C ABI) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(_HERE, "csrc")
+LIB = os.path.join(_HERE, "libmxq.so")
+SOURCES = ["mxq_api.hip", "stream_kernels.hip", "brute_kernels.hip", "aux_kernels.hip"]
+
+# No fast-math and no FMA contraction: every rounding in the kernels is written out.
+# Packed-fp32 instructions are switched off for the device compiler.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
+         "-ffp-contract=off", "-fno-fast-math",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def build_library(verbose: bool = False) -> str:
+    cmd = ["hipcc", *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building libmxq.so")
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

@@ -1,0 +1,137 @@
+// C ABI of libmxq (see include/mxq.h): host-side validation and dispatch.  No allocation, no
+// synchronisation, no global state.
+#include "../../include/mxq.h"
+#include "mxq_launch.hpp"
+
+#include <cmath>
+#include <cstdint>
+
+namespace {
+
+bool valid_block(int b)
+{
+    return b == 2 || b == 4 || b == 8 || b == 16 || b == 32 || b == 64 || b == 128;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Host copy of the scale decode, for mxq_scale_decode only.
+float host_scale_decode(int fmt, unsigned code)
+{
+    if (fmt == MXQ_SCALE_E8M0) return code == 255u ? NAN : std::ldexp(1.0f, (int)code - 127);
+    int bias, maxc;
+    if (fmt == MXQ_SCALE_E4M3) { bias = 7; maxc = 0x7E; }
+    else if (fmt == MXQ_SCALE_UE5M3) { bias = 15; maxc = 0xFE; }
+    else return NAN;
+    if ((int)code > maxc) return NAN;
+    const int e = (int)(code >> 3), m = (int)(code & 7u);
+    if (e == 0) return std::ldexp((float)m, 1 - bias - 3);
+    return std::ldexp((float)(8 + m), e - bias - 3);
+}
+
+}  // namespace
+
+extern "C" {
+
+int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
+                 int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
+                 uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                 int x_dtype, void* stream)
+{
+    if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
+    if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
+    if (elem_fmt != MXQ_ELEM_E2M1) return MXQ_ERR_INVALID_ARG;
+    if (scale_fmt < MXQ_SCALE_E8M0 || scale_fmt > MXQ_SCALE_UE5M3) return MXQ_ERR_INVALID_ARG;
+    if (recipe < MXQ_RECIPE_ABSMAX || recipe > MXQ_RECIPE_BRUTE) return MXQ_ERR_INVALID_ARG;
+    if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
+    if (!(tensor_scale > 0.0f) || std::isinf(tensor_scale)) return MXQ_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
+    if (scale_fmt == MXQ_SCALE_E8M0 && recipe >= MXQ_RECIPE_4OVER6) return MXQ_ERR_UNSUPPORTED;
+    const int64_t n = rows * cols;
+    if (n == 0) return MXQ_OK;
+    if (!x || !codes_out || !scales_out) return MXQ_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(codes_out, 4) || !aligned(scales_out, 4) ||
+        (sse_out && !aligned(sse_out, 16)))
+        return MXQ_ERR_ALIGNMENT;
+
+    mxq::StreamArgs a;
+    a.x = x; a.n = n; a.dtype = x_dtype; a.block = block; a.scale_fmt = scale_fmt;
+    a.recipe = recipe; a.T = tensor_scale; a.codes = codes_out; a.scales = scales_out;
+    a.sse = sse_out; a.stream = static_cast<hipStream_t>(stream);
+    const hipError_t e = (recipe == MXQ_RECIPE_BRUTE) ? mxq::launch_brute(a) : mxq::launch_stream(a);
+    return e == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
+                   int64_t rows, int64_t cols, int block,
+                   int elem_fmt, int scale_fmt, float tensor_scale,
+                   void* x_out, int out_dtype, void* stream)
+{
+    if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
+    if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
+    if (elem_fmt != MXQ_ELEM_E2M1) return MXQ_ERR_INVALID_ARG;
+    if (scale_fmt < MXQ_SCALE_E8M0 || scale_fmt > MXQ_SCALE_UE5M3) return MXQ_ERR_INVALID_ARG;
+    if (out_dtype != MXQ_DT_BF16 && out_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
+    if (!(tensor_scale > 0.0f) || std::isinf(tensor_scale)) return MXQ_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
+    const int64_t n = rows * cols;
+    if (n == 0) return MXQ_OK;
+    if (!codes || !scales || !x_out) return MXQ_ERR_INVALID_ARG;
+    if (!aligned(codes, 4) || !aligned(scales, 4) || !aligned(x_out, 16)) return MXQ_ERR_ALIGNMENT;
+
+    mxq::DequantArgs a;
+    a.codes = codes; a.scales = scales; a.n = n; a.block = block; a.scale_fmt = scale_fmt;
+    a.dtype = out_dtype; a.T = tensor_scale; a.out = x_out; a.stream = static_cast<hipStream_t>(stream);
+    return mxq::launch_dequant(a) == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                      float* absmax_out, void* stream)
+{
+    if (rows < 0 || cols < 0 || !absmax_out) return MXQ_ERR_INVALID_ARG;
+    if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
+    const int64_t n = rows * cols;
+    if (n > 0 && !x) return MXQ_ERR_INVALID_ARG;
+    if ((n > 0 && !aligned(x, 16)) || !aligned(absmax_out, 4)) return MXQ_ERR_ALIGNMENT;
+    return mxq::launch_absmax(x, n, x_dtype, absmax_out, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+float mxq_tensor_scale_from_absmax(float absmax, int elem_fmt, int scale_fmt)
+{
+    if (elem_fmt != MXQ_ELEM_E2M1) return NAN;
+    float sf_max;
+    if (scale_fmt == MXQ_SCALE_E8M0) sf_max = host_scale_decode(scale_fmt, 254);
+    else if (scale_fmt == MXQ_SCALE_E4M3) sf_max = 448.0f;
+    else if (scale_fmt == MXQ_SCALE_UE5M3) sf_max = 114688.0f;
+    else return NAN;
+    if (!(absmax > 0.0f)) return 1.0f;
+    const float denom = 6.0f * sf_max;
+    const float t = absmax / denom;
+    return (t > 0.0f && !std::isinf(t)) ? t : 1.0f;
+}
+
+float mxq_scale_decode(int scale_fmt, uint8_t code) { return host_scale_decode(scale_fmt, code); }
+
+int mxq_num_candidates(int scale_fmt)
+{
+    if (scale_fmt == MXQ_SCALE_E8M0) return 255;
+    if (scale_fmt == MXQ_SCALE_E4M3) return 126;
+    if (scale_fmt == MXQ_SCALE_UE5M3) return 254;
+    return -1;
+}
+
+const char* mxq_status_string(int status)
+{
+    switch (status) {
+        case MXQ_OK: return "MXQ_OK";
+        case MXQ_ERR_INVALID_ARG: return "MXQ_ERR_INVALID_ARG";
+        case MXQ_ERR_UNSUPPORTED: return "MXQ_ERR_UNSUPPORTED";
+        case MXQ_ERR_ALIGNMENT: return "MXQ_ERR_ALIGNMENT";
+        case MXQ_ERR_HIP: return "MXQ_ERR_HIP";
+        default: return "MXQ_ERR_UNKNOWN";
+    }
+}
+
+}  // extern "C"

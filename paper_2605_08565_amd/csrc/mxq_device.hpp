@@ -1,0 +1,196 @@
+// Device-side building blocks of libmxq (gfx950): number formats, exact-decision quotients,
+// E2M1 rounding, wavefront reductions.  Everything here follows Section 2 of "Finer is Better
+// (with the Right Scaling)" (Eq. 1-4); the places where a cheaper instruction sequence
+// replaces a literal IEEE division carry the argument for why every rounding DECISION is
+// unchanged.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mxq {
+
+constexpr int kE8M0 = 0, kE4M3 = 1, kUE5M3 = 2;
+constexpr int kBF16 = 0, kF32 = 1;
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// ---------------------------------------------------------------------------------------
+// 8-bit floating-point scale formats (Background; eps under Eq. 3).
+// ---------------------------------------------------------------------------------------
+template <int FMT> struct ScaleFmt;
+template <> struct ScaleFmt<kE4M3> {
+    static constexpr int kBias = 7;              // eps = 2^(1-7-3) = 2^-9
+    static constexpr int kMaxCode = 0x7E;        // 1.75 * 2^8 = 448
+    static constexpr float kMaxValue = 448.0f;
+};
+template <> struct ScaleFmt<kUE5M3> {
+    static constexpr int kBias = 15;             // eps = 2^-17
+    static constexpr int kMaxCode = 0xFE;        // 1.75 * 2^16
+    static constexpr float kMaxValue = 114688.0f;
+};
+
+// Value of a finite scale code: m * 2^(1-bias-3) below the first binade, else
+// (1 + m/8) * 2^(e-bias), built directly as fp32 bits.
+template <int FMT>
+__device__ __forceinline__ float sf_decode(uint32_t code)
+{
+    constexpr int bias = ScaleFmt<FMT>::kBias;
+    const float sub = (float)(code & 7u) * u2f((uint32_t)(127 + 1 - bias - 3) << 23);
+    const float nrm = u2f((code + ((127u - bias) << 3)) << 20);
+    return (code < 8u) ? sub : nrm;
+}
+
+// Round_SF of Eq. 2: round-to-nearest-even of y >= 0 into the format, clipped to the largest
+// finite value.  Normal range: RNE of the fp32 mantissa to 3 bits by the usual
+// add-half-minus-one-plus-lsb on the bit pattern.  Sub-normal range: adding 2^(emin+20)
+// makes the fp32 adder itself round y to a multiple of eps (ties to even).
+template <int FMT>
+__device__ __forceinline__ uint32_t sf_encode_rne(float y)
+{
+    constexpr int bias = ScaleFmt<FMT>::kBias;
+    y = fminf(y, ScaleFmt<FMT>::kMaxValue);
+    const uint32_t b = f2u(y);
+    const uint32_t nrm = ((b + 0x7FFFFu + ((b >> 20) & 1u)) >> 20) - ((127u - bias) << 3);
+    const float magic = u2f((uint32_t)(127 + (1 - bias) + 20) << 23);
+    const uint32_t sub = f2u(y + magic) - f2u(magic);
+    const float min_normal = u2f((uint32_t)(127 + 1 - bias) << 23);
+    return (y < min_normal) ? sub : nrm;
+}
+
+// ---------------------------------------------------------------------------------------
+// Quotients whose rounding decisions are exact.
+//
+// The method divides in IEEE fp32 (v / S, amax / M) and then rounds the quotient to a very
+// coarse grid (E2M1, or an 8-bit scale format).  Only the side of each grid mid-point t the
+// quotient falls on matters.  For a divisor d with at most 4 significant bits and a
+// mid-point t with at most 5, the product t*d is exact in fp32, and for fp32 v
+//     fl32(v / d) <, =, > t   <=>   v <, =, > t*d,
+// because v != t*d implies |v/(t*d) - 1| >= 2^-24, which is more than half an ulp of t away.
+// The same holds for  y = fl32(v*r_hi + fl32(v*r_lo))  with r_hi + r_lo = 1/d to 2^-47
+// relative: y is within 2^-46 relative of v/d before its single rounding, far inside the
+// 2^-28 margin the inequality above leaves.  So y may stand in for the IEEE quotient
+// wherever only the rounded code is needed.  (The residual v - q*S is computed from v, q and
+// S, never from y.)
+// ---------------------------------------------------------------------------------------
+struct Recip { float hi, lo; };
+
+// r_hi = fl32(1/d) (IEEE division), r_lo = fl32(rho * r_hi) with rho = 1 - r_hi*d exact (fma).
+__device__ __forceinline__ Recip make_recip(float d)
+{
+    Recip r;
+    r.hi = 1.0f / d;
+    const float rho = __builtin_fmaf(-r.hi, d, 1.0f);
+    r.lo = rho * r.hi;
+    return r;
+}
+
+__device__ __forceinline__ float quot(float v, Recip r)
+{
+    return __builtin_fmaf(v, r.hi, v * r.lo);
+}
+
+constexpr float kSixthHi = (float)(1.0 / 6.0);
+constexpr float kSixthLo = (float)(1.0 / 6.0 - (double)kSixthHi);
+
+// ---------------------------------------------------------------------------------------
+// E2M1 (Section 2 value set {0, .5, 1, 1.5, 2, 3, 4, 6}).
+// ---------------------------------------------------------------------------------------
+
+// Magnitude index of the value nearest to ay >= 0; mid-points go to the even index; anything
+// above 5 is 6.
+__device__ __forceinline__ uint32_t e2m1_round_mag(float ay)
+{
+    return (uint32_t)(ay > 0.25f) + (uint32_t)(ay >= 0.75f) + (uint32_t)(ay > 1.25f) +
+           (uint32_t)(ay >= 1.75f) + (uint32_t)(ay > 2.5f) + (uint32_t)(ay >= 3.5f) +
+           (uint32_t)(ay > 5.0f);
+}
+
+// Value of a magnitude index: 0, 0.5, then (1 + m/2) * 2^(e-1) as fp32 bits.
+__device__ __forceinline__ float e2m1_mag_value(uint32_t mag)
+{
+    const float lowv = 0.5f * (float)mag;
+    const float high = u2f((mag + 252u) << 22);
+    return (mag < 2u) ? lowv : high;
+}
+
+// ---------------------------------------------------------------------------------------
+// Wavefront helpers.  A block of more than 8 elements is spread over 2, 4, 8 or 16
+// neighbouring lanes (8 elements each); xor-butterflies inside a 16-lane DPP row combine
+// them.  After a butterfly level every lane of a pair holds the same value, so the mirror
+// patterns (lane i <-> 7-i, i <-> 15-i) deliver the partner group's value for the xor-4 and
+// xor-8 levels.  fp32 addition is commutative, so all lanes of a block end with the same
+// bits, equal to the balanced binary tree in index order.
+// ---------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each group of 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each row of 16
+
+template <int LANES>
+__device__ __forceinline__ float group_max(float v)
+{
+    if constexpr (LANES >= 2) v = fmaxf(v, dpp_f<kDppXor1>(v));
+    if constexpr (LANES >= 4) v = fmaxf(v, dpp_f<kDppXor2>(v));
+    if constexpr (LANES >= 8) v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+    if constexpr (LANES >= 16) v = fmaxf(v, dpp_f<kDppMirror>(v));
+    return v;
+}
+
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v)
+{
+    if constexpr (LANES >= 2) v = v + dpp_f<kDppXor1>(v);
+    if constexpr (LANES >= 4) v = v + dpp_f<kDppXor2>(v);
+    if constexpr (LANES >= 8) v = v + dpp_f<kDppHalfMirror>(v);
+    if constexpr (LANES >= 16) v = v + dpp_f<kDppMirror>(v);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Loads: 8 consecutive elements per lane, widened to fp32.
+// ---------------------------------------------------------------------------------------
+template <int DT> struct Elem;
+template <> struct Elem<kBF16> { using type = uint16_t; };
+template <> struct Elem<kF32> { using type = float; };
+
+template <int DT>
+__device__ __forceinline__ void load8(const void* x, int64_t first, float (&v)[8])
+{
+    if constexpr (DT == kBF16) {
+        const uint4 r = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x) + first);
+        v[0] = u2f(r.x << 16); v[1] = u2f(r.x & 0xFFFF0000u);
+        v[2] = u2f(r.y << 16); v[3] = u2f(r.y & 0xFFFF0000u);
+        v[4] = u2f(r.z << 16); v[5] = u2f(r.z & 0xFFFF0000u);
+        v[6] = u2f(r.w << 16); v[7] = u2f(r.w & 0xFFFF0000u);
+    } else {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(x) + first);
+        const float4 a = p[0], b = p[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+}
+
+// Ragged tail: `count` < 8 valid elements, the rest read as +0.
+template <int DT>
+__device__ __forceinline__ void load_partial(const void* x, int64_t first, int count, float (&v)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float f = 0.0f;
+        if (i < count) {
+            if constexpr (DT == kBF16)
+                f = u2f((uint32_t)static_cast<const uint16_t*>(x)[first + i] << 16);
+            else
+                f = static_cast<const float*>(x)[first + i];
+        }
+        v[i] = f;
+    }
+}
+
+}  // namespace mxq

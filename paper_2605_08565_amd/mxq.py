@@ -1,0 +1,150 @@
+"""Thin Python binding over the C ABI of libmxq (include/mxq.h).
+
+Argument marshalling only: every function takes torch tensors that already live on the GPU,
+passes their device pointers and the current HIP stream to the library and returns.  Nothing
+is computed here and there is no CPU fallback -- a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmxq.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_HIP = 0, -1, -2, -3, -4
+ELEM_E2M1 = 0
+SCALE_E8M0, SCALE_E4M3, SCALE_UE5M3 = 0, 1, 2
+RECIPE_ABSMAX, RECIPE_ABSMAX_PZ, RECIPE_4OVER6, RECIPE_4OVER6_PZ, RECIPE_BRUTE = 0, 1, 2, 3, 4
+DT_BF16, DT_F32 = 0, 1
+
+_lib = None
+
+
+class MxqError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"libmxq: {status_string(status)} ({status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libmxq.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with "
+                          "`python -m paper_2605_08565_amd.build` (hipcc, gfx950)")
+    L = ctypes.CDLL(LIB_PATH)
+    i64, i32, f32, vp, u8 = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_uint8
+    L.mxq_quantize.restype = i32
+    L.mxq_quantize.argtypes = [vp, i64, i64, i32, i32, i32, i32, f32, vp, vp, vp, i32, vp]
+    L.mxq_dequantize.restype = i32
+    L.mxq_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
+    L.mxq_tensor_absmax.restype = i32
+    L.mxq_tensor_absmax.argtypes = [vp, i64, i64, i32, vp, vp]
+    L.mxq_tensor_scale_from_absmax.restype = f32
+    L.mxq_tensor_scale_from_absmax.argtypes = [f32, i32, i32]
+    L.mxq_scale_decode.restype = f32
+    L.mxq_scale_decode.argtypes = [i32, u8]
+    L.mxq_num_candidates.restype = i32
+    L.mxq_num_candidates.argtypes = [i32]
+    L.mxq_status_string.restype = ctypes.c_char_p
+    L.mxq_status_string.argtypes = [i32]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().mxq_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return DT_BF16
+    if t.dtype == torch.float32:
+        return DT_F32
+    raise TypeError("libmxq takes bfloat16 or float32 tensors")
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise MxqError(status)
+
+
+def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_scale: float = 1.0,
+             codes_out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None,
+             sse_out: torch.Tensor | None = None, want_sse: bool = True, stream=None,
+             elem_fmt: int = ELEM_E2M1):
+    """mxq_quantize on a 2-D contiguous CUDA tensor. Returns (codes, scales, sse)."""
+    if not x.is_cuda or x.dim() != 2 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, cols = x.shape
+    dev = x.device
+    if codes_out is None:
+        codes_out = torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev)
+    if scales_out is None:
+        scales_out = torch.empty((rows, cols // block if block > 0 else 0), dtype=torch.uint8, device=dev)
+    if sse_out is None and want_sse:
+        sse_out = torch.empty((rows, cols // block if block > 0 else 0), dtype=torch.float32, device=dev)
+    _check(lib().mxq_quantize(x.data_ptr(), rows, cols, block, elem_fmt, scale_fmt, recipe,
+                              float(tensor_scale), codes_out.data_ptr(), scales_out.data_ptr(),
+                              sse_out.data_ptr() if sse_out is not None else None,
+                              _dtype_code(x), _stream_ptr(stream)))
+    return codes_out, scales_out, sse_out
+
+
+def dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt: int,
+               tensor_scale: float = 1.0, out_dtype: torch.dtype = torch.float32,
+               out: torch.Tensor | None = None, stream=None, elem_fmt: int = ELEM_E2M1) -> torch.Tensor:
+    rows, half = codes.shape
+    cols = half * 2
+    if out is None:
+        out = torch.empty((rows, cols), dtype=out_dtype, device=codes.device)
+    _check(lib().mxq_dequantize(codes.data_ptr(), scales.data_ptr(), rows, cols, block, elem_fmt,
+                                scale_fmt, float(tensor_scale), out.data_ptr(), _dtype_code(out),
+                                _stream_ptr(stream)))
+    return out
+
+
+def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """mxq_tensor_absmax: one-element fp32 device tensor holding max |x|."""
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor on the GPU")
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=x.device)
+    rows = x.shape[0] if x.dim() == 2 else 1
+    cols = x.shape[1] if x.dim() == 2 else x.numel()
+    _check(lib().mxq_tensor_absmax(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
+                                   _stream_ptr(stream)))
+    return out
+
+
+def tensor_scale_from_absmax(absmax: float, scale_fmt: int, elem_fmt: int = ELEM_E2M1) -> float:
+    return float(lib().mxq_tensor_scale_from_absmax(float(absmax), elem_fmt, scale_fmt))
+
+
+def scale_decode(scale_fmt: int, code: int) -> float:
+    return float(lib().mxq_scale_decode(scale_fmt, int(code) & 0xFF))
+
+
+def num_candidates(scale_fmt: int) -> int:
+    return int(lib().mxq_num_candidates(scale_fmt))
+
+
+def from_bits(bits, device="cuda") -> torch.Tensor:
+    """numpy uint16 bf16 bit patterns / float32 array -> GPU tensor holding the same bytes."""
+    import numpy as np
+    a = np.ascontiguousarray(bits)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    if a.dtype == np.float32:
+        return torch.from_numpy(a).to(device)
+    raise TypeError("expected uint16 (bf16 bits) or float32")

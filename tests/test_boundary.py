@@ -1,0 +1,110 @@
+"""The C-ABI library: it loads, exports every symbol the header declares, its host helpers
+agree with the oracle, and every argument error is reported before anything is launched.
+No GPU needed: validation runs on the host and precedes any HIP call."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def mxq():
+    from paper_2605_08565_amd import mxq as M
+    if not os.path.exists(M.LIB_PATH):
+        from paper_2605_08565_amd.build import build_library
+        build_library()
+    M.lib()
+    return M
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mxq.h")).read()
+    return sorted(set(re.findall(r"MXQ_API[^;(]*?\b(mxq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(mxq):
+    names = declared_symbols()
+    assert names == sorted(["mxq_quantize", "mxq_dequantize", "mxq_tensor_absmax",
+                            "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
+                            "mxq_num_candidates", "mxq_status_string"])
+    L = ctypes.CDLL(mxq.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_host_helpers_agree_with_oracle(mxq, oracle):
+    for fmt in (0, 1, 2):
+        assert mxq.num_candidates(fmt) == oracle.num_candidates(fmt)
+        for code in range(256):
+            a, b = mxq.scale_decode(fmt, code), oracle.scale_decode(fmt, code)
+            assert (math.isnan(a) and math.isnan(b)) or a == b, (fmt, code)
+    assert mxq.num_candidates(7) == -1
+    for A in (0.0, 1.0, 250.0, 3.1e-5, 2688.0, 1e30):
+        for fmt in (0, 1, 2):
+            assert mxq.tensor_scale_from_absmax(A, fmt) == oracle.tensor_scale(A, fmt)
+    assert mxq.tensor_scale_from_absmax(2688.0, mxq.SCALE_E4M3) == 1.0
+    assert math.isnan(mxq.tensor_scale_from_absmax(1.0, 9))
+    assert mxq.status_string(0) == "MXQ_OK"
+    assert mxq.status_string(-3) == "MXQ_ERR_ALIGNMENT"
+    assert mxq.status_string(77) == "MXQ_ERR_UNKNOWN"
+
+
+def test_argument_validation_without_a_launch(mxq):
+    L = mxq.lib()
+    P = 0x10000  # a fake, aligned, never-dereferenced device address
+
+    def q(x=P, rows=4, cols=64, block=16, elem=0, fmt=1, rec=0, T=1.0, codes=P, scales=P, sse=P, dt=0):
+        return L.mxq_quantize(x, rows, cols, block, elem, fmt, rec, T, codes, scales, sse, dt, None)
+
+    assert q(x=None) == mxq.ERR_INVALID_ARG
+    assert q(codes=None) == mxq.ERR_INVALID_ARG
+    assert q(scales=None) == mxq.ERR_INVALID_ARG
+    assert q(rows=-1) == mxq.ERR_INVALID_ARG
+    assert q(block=3) == mxq.ERR_INVALID_ARG
+    assert q(block=256) == mxq.ERR_INVALID_ARG
+    assert q(cols=72, block=16) == mxq.ERR_INVALID_ARG
+    assert q(elem=1) == mxq.ERR_INVALID_ARG
+    assert q(fmt=3) == mxq.ERR_INVALID_ARG
+    assert q(rec=5) == mxq.ERR_INVALID_ARG
+    assert q(dt=2) == mxq.ERR_INVALID_ARG
+    for T in (0.0, -1.0, float("inf"), float("nan")):
+        assert q(T=T) == mxq.ERR_INVALID_ARG
+    assert q(fmt=0, rec=2) == mxq.ERR_UNSUPPORTED
+    assert q(fmt=0, rec=4) == mxq.ERR_UNSUPPORTED
+    assert q(x=P + 2) == mxq.ERR_ALIGNMENT
+    assert q(codes=P + 1) == mxq.ERR_ALIGNMENT
+    assert q(scales=P + 2) == mxq.ERR_ALIGNMENT
+    assert q(sse=P + 4) == mxq.ERR_ALIGNMENT
+    assert q(rows=1 << 40, cols=1 << 40) == mxq.ERR_INVALID_ARG
+    # empty tensors are a valid no-op, also with NULL pointers
+    assert q(rows=0) == mxq.OK
+    assert q(rows=0, x=None, codes=None, scales=None, sse=None) == mxq.OK
+    assert q(rows=3, cols=0) == mxq.OK
+
+    def d(codes=P, scales=P, rows=4, cols=64, block=16, elem=0, fmt=1, T=1.0, out=P, dt=1):
+        return L.mxq_dequantize(codes, scales, rows, cols, block, elem, fmt, T, out, dt, None)
+
+    assert d(codes=None) == mxq.ERR_INVALID_ARG
+    assert d(out=None) == mxq.ERR_INVALID_ARG
+    assert d(block=5) == mxq.ERR_INVALID_ARG
+    assert d(fmt=-1) == mxq.ERR_INVALID_ARG
+    assert d(dt=3) == mxq.ERR_INVALID_ARG
+    assert d(T=0.0) == mxq.ERR_INVALID_ARG
+    assert d(out=P + 8) == mxq.ERR_ALIGNMENT
+    assert d(rows=0) == mxq.OK
+
+    assert L.mxq_tensor_absmax(P, 4, 4, 0, None, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax(None, 4, 4, 0, P, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax(P, 4, 4, 5, P, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax(P + 4, 4, 4, 0, P, None) == mxq.ERR_ALIGNMENT
+
+
+def test_binding_fails_loudly_without_the_library(mxq, monkeypatch):
+    monkeypatch.setattr(mxq, "_lib", None)
+    monkeypatch.setattr(mxq, "LIB_PATH", "/nonexistent/libmxq.so")
+    with pytest.raises(ImportError):
+        mxq.lib()

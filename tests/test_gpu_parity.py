@@ -1,0 +1,287 @@
+"""GPU parity: libmxq (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: codes and scale bytes bit-exact; per-block SSE bit-exact (both sides use the same fp32
+tree); per-tensor MSE within 1e-6 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_08565_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+FMT_NAMES = {0: "e8m0", 1: "e4m3", 2: "ue5m3"}
+REC_NAMES = {0: "absmax", 1: "absmax_pz", 2: "4over6", 3: "4over6_pz", 4: "brute"}
+BLOCKS = (2, 4, 8, 16, 32, 64, 128)
+
+
+@pytest.fixture(scope="module")
+def mxq():
+    from paper_2605_08565_amd import mxq as M
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    M.lib()
+    return M
+
+
+def combos(brute=True):
+    out = [(0, 0)]
+    for fmt in (1, 2):
+        for rec in (0, 1, 2, 3) + ((4,) if brute else ()):
+            out.append((fmt, rec))
+    return out
+
+
+def run_gpu(mxq, x_np, block, fmt, rec, T=1.0):
+    x = mxq.from_bits(x_np)
+    c, s, e = mxq.quantize(x, block, fmt, rec, tensor_scale=T)
+    torch.cuda.synchronize()
+    return c.cpu().numpy(), s.cpu().numpy(), e.cpu().numpy()
+
+
+def check(oracle, mxq, x_np, block, fmt, rec, T=1.0, tag=""):
+    print(f"[parity] {tag} shape={x_np.shape} dtype={x_np.dtype} b={block} fmt={FMT_NAMES[fmt]} "
+          f"recipe={REC_NAMES[rec]} T={T}", flush=True)
+    gc, gs, ge = run_gpu(mxq, x_np, block, fmt, rec, T)
+    oc, os_, oe = oracle.quantize(x_np, block, fmt, rec, tensor_scale=T)
+    assert (gs == os_).all(), f"scale bytes differ in {(gs != os_).sum()} blocks"
+    assert (gc == oc).all(), f"code bytes differ in {(gc != oc).sum()} bytes"
+    assert (ge.view(np.uint32) == oe.view(np.uint32)).all(), "block SSE not bit-identical"
+    if x_np.size:
+        m_g, m_o = oracle.tensor_mse(ge, x_np.size, T), oracle.tensor_mse(oe, x_np.size, T)
+        if np.isfinite(m_o):
+            assert abs(m_g - m_o) <= 1e-6 * abs(m_o)
+
+
+# ------------------------------------------------------------------ small, every combination
+
+@pytest.mark.parametrize("block", BLOCKS)
+def test_all_recipes_bf16_weights(oracle, mxq, block):
+    """37 x 1152 spans several workgroup tiles (9 wavefronts of chunks per 2 rows) and ends
+    inside a wavefront."""
+    x = W.student_t_weights(37, 1152, seed=100 + block)
+    for fmt, rec in combos():
+        check(oracle, mxq, x, block, fmt, rec, tag="weights")
+
+
+@pytest.mark.parametrize("block", BLOCKS)
+def test_all_recipes_f32_normal(oracle, mxq, block):
+    x = W.normal_f32(19, 640, seed=200 + block, sigma=0.004)
+    x[3] *= 300.0
+    x[7] *= 1e-3
+    for fmt, rec in combos():
+        check(oracle, mxq, x, block, fmt, rec, tag="normal-f32")
+
+
+@pytest.mark.parametrize("block", (4, 16, 64))
+def test_hierarchical_small(oracle, mxq, block):
+    x = W.outlier_activations(48, 1024, seed=300 + block)
+    xt = mxq.from_bits(x)
+    A = float(mxq.tensor_absmax(xt).cpu()[0])
+    assert A == oracle.tensor_absmax(x)
+    for fmt in (1, 2):
+        T = mxq.tensor_scale_from_absmax(A, fmt)
+        assert T == oracle.tensor_scale(A, fmt)
+        for rec in (0, 1, 2, 3, 4):
+            check(oracle, mxq, x, block, fmt, rec, T=T, tag="hierarchical")
+    check(oracle, mxq, W.bf16_bits_to_f32(x), block, 1, 2, T=mxq.tensor_scale_from_absmax(A, 1),
+          tag="hierarchical-f32")
+
+
+def test_config1_full(oracle, mxq):
+    """fp32 1024 x 4096, N(0,1), E2M1, block 16, unsigned E4M3, abs-max: the whole tensor."""
+    x = W.config1()
+    check(oracle, mxq, x, 16, 1, 0, tag="config1")
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_ragged_and_tiny_shapes(oracle, mxq):
+    rng = np.random.default_rng(7)
+    for rows, cols, block in [(1, 2, 2), (3, 6, 2), (1, 4, 4), (5, 12, 4), (7, 10, 2), (1, 8, 8),
+                              (3, 24, 8), (1, 16, 16), (1, 128, 128), (65, 20, 4), (513, 18, 2)]:
+        x32 = (rng.standard_normal((rows, cols)) * 0.05).astype(np.float32)
+        for x in (x32, W.f32_to_bf16_bits(x32)):
+            for fmt, rec in combos():
+                check(oracle, mxq, x, block, fmt, rec, tag="ragged")
+
+
+def test_empty(mxq):
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    c, s, e = mxq.quantize(x, 16, 1, 0)
+    assert c.shape == (0, 32) and s.shape == (0, 4) and e.shape == (0, 4)
+    out = mxq.dequantize(c, s, 16, 1)
+    assert out.shape == (0, 64)
+    assert float(mxq.tensor_absmax(x).cpu()[0]) == 0.0
+
+
+def test_special_values(oracle, mxq):
+    """Zero blocks, signed zeros, sub-normals, values that clip the scale format, exact ties."""
+    rows = []
+    rows.append(np.zeros(128, np.float32))
+    z = np.zeros(128, np.float32); z[1::2] = -0.0; rows.append(z)
+    rows.append(np.full(128, 1e-41, np.float32))
+    rows.append(np.full(128, 2.0 ** -126, np.float32))
+    rows.append(np.tile(np.float32([3e4, -1e6, 2.5e5, 7e9, -3e38, 1e38, 6 * 448.0, 6 * 448.1]), 16))
+    ties = np.float32([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 6.0])
+    rows.append(np.tile(ties, 16))
+    rows.append(np.tile(-ties * 0.8125, 16))
+    rows.append(np.tile(np.nextafter(ties * np.float32(1.375), np.float32(0)), 16))
+    rows.append(np.tile(np.float32([2 ** -10 * 6, 2 ** -10 * 4, 2 ** -9, 2 ** -11, 0, 0, 0, 0]), 16))
+    rows.append(np.tile(np.float32([2 ** -18 * 6, 2 ** -18 * 4, 2 ** -17, 2 ** -19, 0, 0, 0, 0]), 16))
+    x = np.stack(rows)
+    for block in (2, 8, 16, 128):
+        for fmt, rec in combos():
+            check(oracle, mxq, x, block, fmt, rec, tag="special")
+    xb = W.f32_to_bf16_bits(x)
+    for block in (4, 32):
+        for fmt, rec in combos():
+            check(oracle, mxq, xb, block, fmt, rec, tag="special-bf16")
+
+
+def test_sse_out_may_be_null(oracle, mxq):
+    x_np = W.student_t_weights(16, 256, seed=5)
+    x = mxq.from_bits(x_np)
+    for rec in (0, 2, 4):
+        c, s, e = mxq.quantize(x, 16, 1, rec, want_sse=False)
+        assert e is None
+        oc, os_, _ = oracle.quantize(x_np, 16, 1, rec)
+        assert (c.cpu().numpy() == oc).all() and (s.cpu().numpy() == os_).all()
+
+
+def test_non_default_stream_and_determinism(mxq):
+    x = mxq.from_bits(W.student_t_weights(256, 2048, seed=6))
+    st = torch.cuda.Stream()
+    ref = None
+    for _ in range(3):
+        with torch.cuda.stream(st):
+            c, s, e = mxq.quantize(x, 16, 1, 2)
+        st.synchronize()
+        cur = (c.cpu(), s.cpu(), e.cpu())
+        if ref is not None:
+            assert all(torch.equal(a, b) for a, b in zip(ref, cur))
+        ref = cur
+
+
+# ------------------------------------------------------------------ de-quantise, abs-max
+
+@pytest.mark.parametrize("block", (2, 16, 128))
+def test_dequantize(oracle, mxq, block):
+    rng = np.random.default_rng(block)
+    rows, cols = 9, 384
+    codes = rng.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)
+    for fmt, hi in ((0, 255), (1, 0x7F), (2, 0xFF)):
+        lo = 110 if fmt == 0 else 0
+        top = 140 if fmt == 0 else hi
+        scales = rng.integers(lo, top, size=(rows, cols // block), dtype=np.uint8)
+        for T in (1.0, 0.0731):
+            for dt, tdt in ((oracle.DT_F32, torch.float32), (oracle.DT_BF16, torch.bfloat16)):
+                want = oracle.dequantize(codes, scales, block, fmt, T, dt)
+                got = mxq.dequantize(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(),
+                                     block, fmt, T, tdt)
+                g = got.cpu()
+                g = g.numpy() if tdt == torch.float32 else g.view(torch.int16).numpy().view(np.uint16)
+                if tdt == torch.float32:
+                    assert (g.view(np.uint32) == want.view(np.uint32)).all()
+                else:
+                    assert (g == want).all()
+
+
+def test_dequantize_roundtrip_ragged(oracle, mxq):
+    x = W.student_t_weights(5, 12, seed=8)
+    c, s, _ = oracle.quantize(x, 4, 1, 0)
+    want = oracle.dequantize(c, s, 4, 1)
+    got = mxq.dequantize(torch.from_numpy(c).cuda(), torch.from_numpy(s).cuda(), 4, 1).cpu().numpy()
+    assert (got == want).all()
+
+
+def test_tensor_absmax(oracle, mxq):
+    for x in (W.config1()[:37], W.student_t_weights(33, 1000, seed=9), W.normal_f32(1, 6, 3)):
+        got = float(mxq.tensor_absmax(mxq.from_bits(x)).cpu()[0])
+        assert got == oracle.tensor_absmax(x)
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+def sample_rows(n_rows, k, seed):
+    rng = np.random.default_rng(seed)
+    mid = rng.choice(np.arange(1, n_rows - 1), size=k - 2, replace=False)
+    return np.sort(np.concatenate([[0, n_rows - 1], mid]))
+
+
+def check_rows(oracle, x_np, rows, gpu_out, block, fmt, rec, T=1.0):
+    gc, gs, ge = gpu_out
+    idx = torch.from_numpy(rows).cuda()
+    gc, gs, ge = gc[idx].cpu().numpy(), gs[idx].cpu().numpy(), ge[idx].cpu().numpy()
+    oc, os_, oe = oracle.quantize(np.ascontiguousarray(x_np[rows]), block, fmt, rec, tensor_scale=T)
+    assert (gs == os_).all() and (gc == oc).all()
+    assert (ge.view(np.uint32) == oe.view(np.uint32)).all()
+
+
+def test_config2_full_size_sampled(oracle, mxq):
+    """bf16 4096 x 14336 Student-t weights, the launch configuration the benchmark times.
+    The oracle checks 24 whole rows (first, last, 22 seeded) per run; the SSE chain
+    abs-max >= 4-over-6 holds on every block of the tensor."""
+    x_np = W.config2()
+    x = mxq.from_bits(x_np)
+    rows = sample_rows(x_np.shape[0], 24, seed=2)
+    for block in (8, 16, 32, 64):
+        outs = {}
+        for rec in (0, 1, 2):
+            print(f"[parity] config2 b={block} recipe={REC_NAMES[rec]}", flush=True)
+            outs[rec] = mxq.quantize(x, block, 1, rec)
+            torch.cuda.synchronize()
+            check_rows(oracle, x_np, rows, outs[rec], block, 1, rec)
+        assert bool((outs[0][2] >= outs[2][2]).all())
+        assert bool((outs[0][2] >= outs[1][2]).all())
+
+
+def test_config3_full_size_sampled(oracle, mxq):
+    """bf16 8192 x 4096 activations with outlier channels, hierarchical scaling."""
+    x_np = W.config3()
+    x = mxq.from_bits(x_np)
+    A = float(mxq.tensor_absmax(x).cpu()[0])
+    assert A == oracle.tensor_absmax(x_np)
+    T = mxq.tensor_scale_from_absmax(A, 1)
+    rows = sample_rows(x_np.shape[0], 24, seed=3)
+    for block in (4, 8, 16, 32, 64):
+        for rec in (0, 2):
+            print(f"[parity] config3 b={block} recipe={REC_NAMES[rec]} T={T}", flush=True)
+            out = mxq.quantize(x, block, 1, rec, tensor_scale=T)
+            torch.cuda.synchronize()
+            check_rows(oracle, x_np, rows, out, block, 1, rec, T=T)
+
+
+def test_config4_brute_full_size_sampled(oracle, mxq):
+    """Brute-force search on the full 4096 x 14336 weights; the oracle checks 6 whole rows per
+    run; brute-force SSE <= 4-over-6 SSE <= abs-max SSE on every block."""
+    x_np = W.config2()
+    x = mxq.from_bits(x_np)
+    rows = sample_rows(x_np.shape[0], 6, seed=4)
+    for block in (4, 16):
+        ab = mxq.quantize(x, block, 1, 0)[2]
+        f6 = mxq.quantize(x, block, 1, 2)[2]
+        for fmt in (1, 2):
+            print(f"[parity] config4 b={block} fmt={FMT_NAMES[fmt]} brute", flush=True)
+            out = mxq.quantize(x, block, fmt, 4)
+            torch.cuda.synchronize()
+            check_rows(oracle, x_np, rows, out, block, fmt, 4)
+            if fmt == 1:
+                assert bool((out[2] <= f6).all()) and bool((f6 <= ab).all())
+
+
+def test_config5_layer0_sampled(oracle, mxq):
+    """Layer 0 of the synthetic 32-layer model, every matrix, every recipe and block size;
+    8 sampled rows per matrix (2 for brute force)."""
+    for name in W.LAYER_SHAPES:
+        x_np = W.layer_matrix(0, name)
+        x = mxq.from_bits(x_np)
+        rows = sample_rows(x_np.shape[0], 8, seed=5)
+        for block in BLOCKS:
+            for fmt, rec in [(0, 0), (1, 0), (1, 1), (1, 2), (2, 0), (1, 4)]:
+                print(f"[parity] config5 {name} b={block} fmt={FMT_NAMES[fmt]} "
+                      f"recipe={REC_NAMES[rec]}", flush=True)
+                out = mxq.quantize(x, block, fmt, rec)
+                torch.cuda.synchronize()
+                r = rows[:2] if rec == 4 else rows
+                check_rows(oracle, x_np, r, out, block, fmt, rec)
