@@ -1,144 +1,237 @@
 // Brute-force scale search (last paragraph of Section 2): for every block, every finite,
 // strictly positive scale code is tried; the code of minimal block SSE wins, the lowest code
-// on a tie.  Same lane mapping as the streaming kernels (8 elements per lane); the tensor is
-// read once and each candidate costs only ALU work, so this kernel is bound by the fp32
+// on a tie.  Same lane mapping as the streaming kernels (8 elements per lane).  The tensor is
+// read once and every candidate costs only ALU work, so this kernel is bound by the fp32
 // vector units, not by HBM.
+//
+// A scale is S = m * 2^e with m in {1, 1.125, .., 1.875}.  Dividing by 2^e commutes with
+// rounding, so the quotient v / S is formed once per mantissa (w_m = v / m, 7 divisions per
+// element instead of one per candidate) and the E2M1 conversion instruction applies 2^e.
+// The inverse conversion returns q * 2^e, and the residual v - (q * 2^e) * m needs a single
+// FMA because the product is exact.  Candidates are visited in ascending code order, so a
+// strict "less than" keeps the lowest code on ties.
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"
 
 namespace mxq {
 
-struct __align__(16) BruteEntry { float S, rhi, rlo, pad; };
+// hi/lo split of 1/m for m = 1 + i/8 (see "Quotients whose rounding decisions are exact").
+__device__ constexpr float mant_value(int i) { return 1.0f + (float)i * 0.125f; }
+__device__ constexpr float mant_rhi(int i) { return (float)(1.0 / (1.0 + i * 0.125)); }
+__device__ constexpr float mant_rlo(int i)
+{
+    return (float)(1.0 / (1.0 + i * 0.125) - (double)(float)(1.0 / (1.0 + i * 0.125)));
+}
 
 template <int B>
-__device__ __forceinline__ void brute_block_sse(const float (&sq)[8], float (&sse)[4])
+struct BruteState {
+    static constexpr int NBLK = (B < 8) ? 8 / B : 1;
+    float best_sse[NBLK];
+    uint32_t best_code[NBLK];
+};
+
+// SSE of the lane's blocks under S = mant_value(MI) * scale2 (scale2 a power of two), and the
+// running arg-min.  w holds the lane's quotients v / mant_value(MI).
+template <int B, int MI>
+__device__ __forceinline__ void try_candidate(const float (&v)[8], const float (&w)[8], float scale2,
+                                              uint32_t code, BruteState<B>& st)
 {
+    constexpr int NBLK = BruteState<B>::NBLK;
+    const uint32_t packed = e2m1_pack8(w, scale2);
+    float q2[8], sq[8];
+    e2m1_unpack8(packed, scale2, q2);                                  // q * 2^e
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float e;
+        if constexpr (MI == 0) e = v[j] - q2[j];
+        else e = __builtin_fmaf(-q2[j], mant_value(MI), v[j]);
+        sq[j] = e * e;
+    }
     const float p0 = sq[0] + sq[1], p1 = sq[2] + sq[3], p2 = sq[4] + sq[5], p3 = sq[6] + sq[7];
+    float s[4];
     if constexpr (B == 2) {
-        sse[0] = p0; sse[1] = p1; sse[2] = p2; sse[3] = p3;
+        s[0] = p0; s[1] = p1; s[2] = p2; s[3] = p3;
     } else if constexpr (B == 4) {
-        sse[0] = p0 + p1; sse[1] = p2 + p3;
+        s[0] = p0 + p1; s[1] = p2 + p3;
     } else {
-        sse[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
+        s[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
+    }
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        const bool better = s[k] < st.best_sse[k];
+        st.best_sse[k] = better ? s[k] : st.best_sse[k];
+        st.best_code[k] = better ? code : st.best_code[k];
     }
 }
 
-template <int DT, int B, int FMT>
+template <int B, int FMT, int MI>
+__device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)[8][8], float scale2,
+                                           uint32_t code0, BruteState<B>& st)
+{
+    if constexpr (MI < 8) {
+        if (code0 + MI <= (uint32_t)ScaleFmt<FMT>::kMaxCode)            // skips the NaN code only
+            try_candidate<B, MI>(v, w[MI], scale2, code0 + MI, st);
+        try_binade<B, FMT, MI + 1>(v, w, scale2, code0, st);
+    }
+}
+
+// Full search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE.
+template <int B, int FMT>
+__device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
+{
+    constexpr int NBLK = BruteState<B>::NBLK;
+    constexpr int EPB = (B < 8) ? B : 8;
+    constexpr int bias = ScaleFmt<FMT>::kBias;
+    constexpr int emin = 1 - bias;                                      // exponent of the first binade
+
+    float w[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[0][j] = v[j];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[i][j] = quot(v[j], Recip{mant_rhi(i), mant_rlo(i)});
+    }
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = 1u; }
+
+    // sub-normal codes 1..7 = j * 2^(emin-3): 1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4
+    const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
+    const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
+    const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
+    try_candidate<B, 0>(v, w[0], s1, 1u, st);
+    try_candidate<B, 0>(v, w[0], s2, 2u, st);
+    try_candidate<B, 4>(v, w[4], s2, 3u, st);
+    try_candidate<B, 0>(v, w[0], s4, 4u, st);
+    try_candidate<B, 2>(v, w[2], s4, 5u, st);
+    try_candidate<B, 4>(v, w[4], s4, 6u, st);
+    try_candidate<B, 6>(v, w[6], s4, 7u, st);
+
+    // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
+    for (uint32_t ef = 1u; ef <= ((uint32_t)ScaleFmt<FMT>::kMaxCode >> 3); ++ef) {
+        const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
+        try_binade<B, FMT, 0>(v, w, scale2, ef << 3, st);
+    }
+
+    // codes of the winners
+    float y[8];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        const Recip r = make_recip(sf_decode<FMT>(st.best_code[k]));
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
+    }
+    packed = e2m1_pack8(y, 1.0f);
+}
+
+template <int DT, int B, int FMT, bool HAS_T>
 __global__ void __launch_bounds__(kThreads)
-brute_kernel(const void* __restrict__ x, int64_t n, float T,
+brute_kernel(const void* __restrict__ x, int64_t n_full, float T,
              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
-    constexpr int NBLK = (B < 8) ? 8 / B : 1;
+    constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
-    constexpr int EPB = (B < 8) ? B : 8;
-    constexpr uint32_t kMax = ScaleFmt<FMT>::kMaxCode;
 
-    __shared__ BruteEntry tab[256];
-    for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
-        BruteEntry e{0.0f, 0.0f, 0.0f, 0.0f};
-        if (c >= 1u && c <= kMax) {
-            e.S = sf_decode<FMT>(c);
-            const Recip r = make_recip(e.S);
-            e.rhi = r.hi;
-            e.rlo = r.lo;
-        }
-        tab[c] = e;
-    }
-    __syncthreads();
-
-    const int64_t n_chunks = (n + 7) >> 3;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    const int64_t wave_first = (int64_t)blockIdx.x * kThreads + (threadIdx.x & ~63);
+    int64_t chunk = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int64_t base = chunk - (threadIdx.x & 63);
 
-    for (int64_t base = wave_first; base < n_chunks; base += stride) {
-        const int64_t chunk = base + (threadIdx.x & 63);
-        const int64_t first = chunk << 3;
-        const int count = (int)min((int64_t)8, n - first);
+    for (; base < n_full; base += stride, chunk += stride) {
         float v[8];
-        if (count == 8) load8<DT>(x, first, v);
-        else load_partial<DT>(x, first, count, v);
-        if (T != 1.0f) {
+        if (chunk < n_full) load8<DT>(x, chunk << 3, v);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = 0.0f;
+        }
+        if constexpr (HAS_T) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = v[i] / T;
         }
+        uint32_t packed;
+        BruteState<B> st;
+        brute_search<B, FMT>(v, packed, st);
 
-        float best_sse[NBLK];
-        uint32_t best_code[NBLK];
-#pragma unroll
-        for (int k = 0; k < NBLK; ++k) { best_sse[k] = __builtin_inff(); best_code[k] = 1u; }
-
-        for (uint32_t c = 1u; c <= kMax; ++c) {          // ascending: a tie keeps the lowest code
-            const BruteEntry se = tab[c];
-            const Recip r{se.rhi, se.rlo};
-            float sq[8], s[4];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float y = quot(v[j], r);
-                const uint32_t mag = e2m1_round_mag(__builtin_fabsf(y));
-                const float q = u2f(f2u(e2m1_mag_value(mag)) | (f2u(v[j]) & 0x80000000u));
-                const float e = __builtin_fmaf(-q, se.S, v[j]);
-                sq[j] = e * e;
-            }
-            brute_block_sse<B>(sq, s);
-#pragma unroll
-            for (int k = 0; k < NBLK; ++k) {
-                if (s[k] < best_sse[k]) { best_sse[k] = s[k]; best_code[k] = c; }
-            }
-        }
-
-        // codes of the winning candidate
-        uint32_t packed = 0u;
-#pragma unroll
-        for (int k = 0; k < NBLK; ++k) {
-            const BruteEntry se = tab[best_code[k]];
-            const Recip r{se.rhi, se.rlo};
-#pragma unroll
-            for (int i = 0; i < EPB; ++i) {
-                const int j = k * EPB + i;
-                const uint32_t mag = e2m1_round_mag(__builtin_fabsf(quot(v[j], r)));
-                packed |= (((f2u(v[j]) >> 31) << 3) | mag) << (4 * j);
-            }
-        }
-
-        if (count <= 0) continue;
-        if (count == 8) {
+        if (chunk < n_full) {
             codes[chunk] = packed;
-        } else {
-            uint8_t* cb = reinterpret_cast<uint8_t*>(codes) + chunk * 4;
-            for (int i = 0; i < count / 2; ++i) cb[i] = (uint8_t)(packed >> (8 * i));
-        }
-        if constexpr (B >= 8) {
-            if ((threadIdx.x & (LANES - 1)) == 0) {
-                const int64_t blk = chunk / LANES;
-                scales[blk] = (uint8_t)best_code[0];
-                if (sse_out) sse_out[blk] = best_sse[0];
-            }
-        } else {
-            const int64_t blk0 = chunk * NBLK;
-            const int nvalid = count / B;
-            for (int k = 0; k < NBLK; ++k) {
-                if (k < nvalid) {
-                    scales[blk0 + k] = (uint8_t)best_code[k];
-                    if (sse_out) sse_out[blk0 + k] = best_sse[k];
+            if constexpr (B >= 8) {
+                if ((threadIdx.x & (LANES - 1)) == 0) {
+                    const int64_t blk = chunk / LANES;
+                    scales[blk] = (uint8_t)st.best_code[0];
+                    if (sse_out) sse_out[blk] = st.best_sse[0];
+                }
+            } else {
+                const int64_t blk0 = chunk * NBLK;
+#pragma unroll
+                for (int k = 0; k < NBLK; ++k) {
+                    scales[blk0 + k] = (uint8_t)st.best_code[k];
+                    if (sse_out) sse_out[blk0 + k] = st.best_sse[k];
                 }
             }
         }
     }
 }
 
+// Ragged tail (n not a multiple of 8; b = 2 or 4 only): lane 0 of one wavefront.
+template <int DT, int B, int FMT, bool HAS_T>
+__global__ void __launch_bounds__(64)
+brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T,
+                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+{
+    constexpr int NBLK = BruteState<B>::NBLK;
+    float v[8];
+    load_partial<DT>(x, first, (threadIdx.x == 0) ? count : 0, v);
+    if constexpr (HAS_T) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = v[i] / T;
+    }
+    uint32_t packed;
+    BruteState<B> st;
+    brute_search<B, FMT>(v, packed, st);
+    if (threadIdx.x != 0) return;
+    for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
+    for (int k = 0; k < NBLK; ++k) {
+        if (k < count / B) {
+            scales[first / B + k] = (uint8_t)st.best_code[k];
+            if (sse_out) sse_out[first / B + k] = st.best_sse[k];
+        }
+    }
+}
+
+template <int DT, int B, int FMT>
+static hipError_t launch_f(const StreamArgs& a)
+{
+    const int64_t n_full = a.n / 8;
+    const int count = (int)(a.n - n_full * 8);
+    const bool has_t = (a.T != 1.0f);
+    if (n_full > 0) {
+        const int64_t need = (n_full + kThreads - 1) / kThreads;
+        const dim3 grid((unsigned)(need < 256 * 8 ? need : 256 * 8)), block(kThreads);
+        if (has_t)
+            hipLaunchKernelGGL((brute_kernel<DT, B, FMT, true>), grid, block, 0, a.stream,
+                               a.x, n_full, a.T, (uint32_t*)a.codes, a.scales, a.sse);
+        else
+            hipLaunchKernelGGL((brute_kernel<DT, B, FMT, false>), grid, block, 0, a.stream,
+                               a.x, n_full, a.T, (uint32_t*)a.codes, a.scales, a.sse);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if constexpr (B < 8) {
+        if (count > 0) {
+            if (has_t)
+                hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, true>), dim3(1), dim3(64), 0, a.stream,
+                                   a.x, n_full * 8, count, a.T, a.codes, a.scales, a.sse);
+            else
+                hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, false>), dim3(1), dim3(64), 0, a.stream,
+                                   a.x, n_full * 8, count, a.T, a.codes, a.scales, a.sse);
+        }
+    }
+    return hipGetLastError();
+}
+
 template <int DT, int B>
 static hipError_t launch_b(const StreamArgs& a)
 {
-    const int64_t n_chunks = (a.n + 7) / 8;
-    const int64_t need = (n_chunks + kThreads - 1) / kThreads;
-    const int grid = (int)(need < 1 ? 1 : (need < 256 * 8 ? need : 256 * 8));
-    if (a.scale_fmt == kE4M3)
-        hipLaunchKernelGGL((brute_kernel<DT, B, kE4M3>), dim3(grid), dim3(kThreads), 0, a.stream,
-                           a.x, a.n, a.T, (uint32_t*)a.codes, a.scales, a.sse);
-    else
-        hipLaunchKernelGGL((brute_kernel<DT, B, kUE5M3>), dim3(grid), dim3(kThreads), 0, a.stream,
-                           a.x, a.n, a.T, (uint32_t*)a.codes, a.scales, a.sse);
-    return hipGetLastError();
+    return (a.scale_fmt == kE4M3) ? launch_f<DT, B, kE4M3>(a) : launch_f<DT, B, kUE5M3>(a);
 }
 
 template <int DT>

@@ -90,6 +90,25 @@ __device__ __forceinline__ float quot(float v, Recip r)
     return __builtin_fmaf(v, r.hi, v * r.lo);
 }
 
+// (scale value, reciprocal hi/lo) for every scale byte, filled once per workgroup into LDS.
+struct __align__(16) ScaleEntry { float S, rhi, rlo, pad; };
+
+template <int FMT>
+__device__ __forceinline__ void fill_scale_table(ScaleEntry* tab)
+{
+    for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
+        ScaleEntry e{0.0f, 0.0f, 0.0f, 0.0f};
+        if (c >= 1u && c <= (uint32_t)ScaleFmt<FMT>::kMaxCode) {
+            e.S = sf_decode<FMT>(c);
+            const Recip r = make_recip(e.S);
+            e.rhi = r.hi;
+            e.rlo = r.lo;
+        }
+        tab[c] = e;     // code 0: S = 0 and a zero "reciprocal" -> every quotient is a signed 0
+    }
+    __syncthreads();
+}
+
 constexpr float kSixthHi = (float)(1.0 / 6.0);
 constexpr float kSixthLo = (float)(1.0 / 6.0 - (double)kSixthHi);
 
@@ -97,13 +116,47 @@ constexpr float kSixthLo = (float)(1.0 / 6.0 - (double)kSixthHi);
 // E2M1 (Section 2 value set {0, .5, 1, 1.5, 2, 3, 4, 6}).
 // ---------------------------------------------------------------------------------------
 
-// Magnitude index of the value nearest to ay >= 0; mid-points go to the even index; anything
-// above 5 is 6.
-__device__ __forceinline__ uint32_t e2m1_round_mag(float ay)
+// Rounding to E2M1 uses the gfx950 conversion instructions v_cvt_scalef32_pk_fp4_f32 /
+// v_cvt_scalef32_pk_f32_fp4.  The forward one divides two fp32 inputs by a power-of-two scale
+// (only the exponent of the scale operand is used), rounds to nearest even onto
+// {0, .5, 1, 1.5, 2, 3, 4, 6}, saturates at 6, keeps the sign bit also for zero results, and
+// writes the two 4-bit codes (first input in the low nibble) into the selected byte of the
+// destination; the inverse one returns the two values times the scale.  Mid-points go to the
+// even code: 0.25->0, 0.75->1, 1.25->1, 1.75->2, 2.5->2, 3.5->4, 5->4.
+using f32x2 = float __attribute__((ext_vector_type(2)));
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+
+template <int SEL>
+__device__ __forceinline__ uint32_t e2m1_pack2(uint32_t old, float a, float b, float scale)
 {
-    return (uint32_t)(ay > 0.25f) + (uint32_t)(ay >= 0.75f) + (uint32_t)(ay > 1.25f) +
-           (uint32_t)(ay >= 1.75f) + (uint32_t)(ay > 2.5f) + (uint32_t)(ay >= 3.5f) +
-           (uint32_t)(ay > 5.0f);
+    return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(old, a, b, scale, SEL);
+}
+
+template <int SEL>
+__device__ __forceinline__ void e2m1_unpack2(uint32_t packed, float scale, float& a, float& b)
+{
+    const f32x2 r = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(packed, scale, SEL);
+    a = r.x;
+    b = r.y;
+}
+
+// 8 values -> one dword of codes (element j in nibble j).
+__device__ __forceinline__ uint32_t e2m1_pack8(const float (&y)[8], float scale)
+{
+    uint32_t r = 0u;
+    r = e2m1_pack2<0>(r, y[0], y[1], scale);
+    r = e2m1_pack2<1>(r, y[2], y[3], scale);
+    r = e2m1_pack2<2>(r, y[4], y[5], scale);
+    r = e2m1_pack2<3>(r, y[6], y[7], scale);
+    return r;
+}
+
+__device__ __forceinline__ void e2m1_unpack8(uint32_t packed, float scale, float (&q)[8])
+{
+    e2m1_unpack2<0>(packed, scale, q[0], q[1]);
+    e2m1_unpack2<1>(packed, scale, q[2], q[3]);
+    e2m1_unpack2<2>(packed, scale, q[4], q[5]);
+    e2m1_unpack2<3>(packed, scale, q[6], q[7]);
 }
 
 // Value of a magnitude index: 0, 0.5, then (1 + m/2) * 2^(e-1) as fp32 bits.

@@ -4,31 +4,13 @@
 // Mapping: every lane owns 8 consecutive elements (one 128-bit load for bf16, two for fp32),
 // so a block of b >= 8 elements is b/8 neighbouring lanes of one DPP row and a block of
 // b < 8 sits inside a lane.  Per lane the kernel emits one dword of packed codes; the first
-// lane of a block emits the scale byte and the block SSE.  HBM-bound by design: algorithmic
-// traffic is sizeof(in) + 0.5 + 5/b bytes per element.
+// lane of a block emits the scale byte and the block SSE.  The next chunk's load is issued
+// before the current chunk is processed.  HBM-bound by design: algorithmic traffic is
+// sizeof(in) + 0.5 + 5/b bytes per element.
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"
 
 namespace mxq {
-
-// (scale value, reciprocal hi/lo) for every scale byte, filled once per workgroup.
-struct __align__(16) ScaleEntry { float S, rhi, rlo, pad; };
-
-template <int FMT>
-__device__ __forceinline__ void fill_scale_table(ScaleEntry* tab)
-{
-    for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
-        ScaleEntry e{0.0f, 0.0f, 0.0f, 0.0f};
-        if (c >= 1u && c <= (uint32_t)ScaleFmt<FMT>::kMaxCode) {
-            e.S = sf_decode<FMT>(c);
-            const Recip r = make_recip(e.S);
-            e.rhi = r.hi;
-            e.rlo = r.lo;
-        }
-        tab[c] = e;     // code 0: S = 0 and a zero "reciprocal" -> every quotient is 0
-    }
-    __syncthreads();
-}
 
 // Eq. 2 / Eq. 3: scale code from the block abs-max for M = 6 or M = 4.
 template <int FMT, int M>
@@ -51,27 +33,70 @@ __device__ __forceinline__ uint32_t pow2_code(float amax)
     return (uint32_t)max(c, 0);
 }
 
-// Quantise the lane's 8 values (NBLK blocks of EPB elements, one scale code each): packed
-// nibbles and the 8 squared residuals.
+// Quantise the lane's 8 values (NBLK blocks of EPB elements, one scale code each) under
+// table scales: packed nibbles and the 8 squared residuals.
 template <int NBLK, int EPB>
 __device__ __forceinline__ void quant_lane(const float (&v)[8], const uint32_t (&code)[NBLK],
                                            const ScaleEntry* tab, uint32_t& packed, float (&sq)[8])
 {
-    packed = 0u;
+    float y[8], S[NBLK];
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
         const ScaleEntry se = tab[code[k]];
-        const Recip r{se.rhi, se.rlo};
+        S[k] = se.S;
 #pragma unroll
         for (int i = 0; i < EPB; ++i) {
             const int j = k * EPB + i;
-            const float y = quot(v[j], r);
-            const uint32_t mag = e2m1_round_mag(__builtin_fabsf(y));
-            const uint32_t sign = f2u(v[j]) >> 31;
-            const float q = u2f(f2u(e2m1_mag_value(mag)) | (sign << 31));
-            const float e = __builtin_fmaf(-q, se.S, v[j]);    // q*S is exact: one rounding
-            sq[j] = e * e;
-            packed |= ((sign << 3) | mag) << (4 * j);
+            y[j] = quot(v[j], Recip{se.rhi, se.rlo});
+        }
+    }
+    packed = e2m1_pack8(y, 1.0f);
+    float q[8];
+    e2m1_unpack8(packed, 1.0f, q);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float e = __builtin_fmaf(-q[j], S[j / EPB], v[j]);   // q*S is exact: one rounding
+        sq[j] = e * e;
+    }
+}
+
+// One block of EPB < 8 elements inside a lane under the power-of-two scale S: the byte
+// selector of the conversion must be a compile-time constant, hence the unrolled switch.
+template <int NBLK, int EPB>
+__device__ __forceinline__ void pow2_pairs(const float (&v)[8], float S, int k, uint32_t& packed, float (&sq)[8])
+{
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        if (p / (EPB / 2) != k) continue;
+        float q0 = 0.0f, q1 = 0.0f;
+        if (p == 0) { packed = e2m1_pack2<0>(packed, v[0], v[1], S); e2m1_unpack2<0>(packed, S, q0, q1); }
+        if (p == 1) { packed = e2m1_pack2<1>(packed, v[2], v[3], S); e2m1_unpack2<1>(packed, S, q0, q1); }
+        if (p == 2) { packed = e2m1_pack2<2>(packed, v[4], v[5], S); e2m1_unpack2<2>(packed, S, q0, q1); }
+        if (p == 3) { packed = e2m1_pack2<3>(packed, v[6], v[7], S); e2m1_unpack2<3>(packed, S, q0, q1); }
+        const float e0 = v[2 * p] - q0, e1 = v[2 * p + 1] - q1;
+        sq[2 * p] = e0 * e0;
+        sq[2 * p + 1] = e1 * e1;
+    }
+}
+
+// Same under power-of-two scales 2^(code-127): v / 2^k is exact, so the conversion
+// instruction applies the scale itself and the inverse conversion returns q * S.
+template <int NBLK, int EPB>
+__device__ __forceinline__ void quant_lane_pow2(const float (&v)[8], const uint32_t (&code)[NBLK],
+                                                uint32_t& packed, float (&sq)[8])
+{
+    packed = 0u;
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        const float S = (code[k] == 0u) ? u2f(0x00400000u) : u2f(code[k] << 23);
+        if constexpr (NBLK == 1) {
+            packed = e2m1_pack8(v, S);
+            float qS[8];
+            e2m1_unpack8(packed, S, qS);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { const float e = v[j] - qS[j]; sq[j] = e * e; }
+        } else {
+            pow2_pairs<NBLK, EPB>(v, S, k, packed, sq);
         }
     }
 }
@@ -91,134 +116,169 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
     }
 }
 
-template <int DT, int B, int FMT, bool FOUR6>
-__global__ void __launch_bounds__(kThreads)
-stream_kernel(const void* __restrict__ x, int64_t n, float T, int pz,
-              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+// Everything between the load and the store for one lane's 8 values.
+template <int B, int FMT, bool FOUR6, bool HAS_T>
+__device__ __forceinline__ void process_chunk(float (&v)[8], float T, bool pz, const ScaleEntry* tab,
+                                              uint32_t& packed, uint32_t (&code_out)[(B < 8) ? 8 / B : 1],
+                                              float (&sse_sel)[4])
 {
     constexpr int NBLK = (B < 8) ? 8 / B : 1;          // blocks inside one lane
     constexpr int LANES = (B < 8) ? 1 : B / 8;         // lanes per block
     constexpr int EPB = (B < 8) ? B : 8;               // elements of one block inside a lane
 
+    if constexpr (HAS_T) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = v[i] / T;            // IEEE division (hierarchical)
+    }
+
+    float amax[NBLK];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) a = fmaxf(a, __builtin_fabsf(v[k * EPB + i]));
+        amax[k] = group_max<LANES>(a);
+    }
+
+    float sq[8];
+    if constexpr (FMT == kE8M0) {
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) code_out[k] = pow2_code(amax[k]);
+        quant_lane_pow2<NBLK, EPB>(v, code_out, packed, sq);
+        block_sse<B>(sq, sse_sel);
+    } else {
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) code_out[k] = absmax_code<FMT, 6>(amax[k], pz);
+        quant_lane<NBLK, EPB>(v, code_out, tab, packed, sq);
+        block_sse<B>(sq, sse_sel);
+        if constexpr (FOUR6) {
+            uint32_t c4[NBLK], packed4;
+            float sse4[4];
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k) c4[k] = absmax_code<FMT, 4>(amax[k], pz);
+            quant_lane<NBLK, EPB>(v, c4, tab, packed4, sq);
+            block_sse<B>(sq, sse4);
+            // Eq. 4: M = 4 only when its SSE is strictly lower
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k) {
+                if (sse4[k] < sse_sel[k]) {
+                    constexpr uint32_t m = (EPB == 8) ? 0xFFFFFFFFu : ((1u << (4 * EPB)) - 1u);
+                    const uint32_t mask = m << ((4 * EPB * k) & 31);
+                    packed = (packed & ~mask) | (packed4 & mask);
+                    code_out[k] = c4[k];
+                    sse_sel[k] = sse4[k];
+                }
+            }
+        }
+    }
+}
+
+template <int DT> struct RawChunk;
+template <> struct RawChunk<kBF16> { u32x4 a; };
+template <> struct RawChunk<kF32> { u32x4 a, b; };
+
+template <int DT>
+__device__ __forceinline__ RawChunk<DT> load_raw(const void* x, int64_t chunk)
+{
+    RawChunk<DT> r;
+    if constexpr (DT == kBF16) {
+        r.a = __builtin_nontemporal_load(static_cast<const u32x4*>(x) + chunk);
+    } else {
+        r.a = __builtin_nontemporal_load(static_cast<const u32x4*>(x) + 2 * chunk);
+        r.b = __builtin_nontemporal_load(static_cast<const u32x4*>(x) + 2 * chunk + 1);
+    }
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void widen(const RawChunk<DT>& r, float (&v)[8])
+{
+    if constexpr (DT == kBF16) {
+        v[0] = u2f(r.a.x << 16); v[1] = u2f(r.a.x & 0xFFFF0000u);
+        v[2] = u2f(r.a.y << 16); v[3] = u2f(r.a.y & 0xFFFF0000u);
+        v[4] = u2f(r.a.z << 16); v[5] = u2f(r.a.z & 0xFFFF0000u);
+        v[6] = u2f(r.a.w << 16); v[7] = u2f(r.a.w & 0xFFFF0000u);
+    } else {
+        v[0] = u2f(r.a.x); v[1] = u2f(r.a.y); v[2] = u2f(r.a.z); v[3] = u2f(r.a.w);
+        v[4] = u2f(r.b.x); v[5] = u2f(r.b.y); v[6] = u2f(r.b.z); v[7] = u2f(r.b.w);
+    }
+}
+
+// Main kernel: the n_full = n / 8 complete chunks.
+template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
+__global__ void __launch_bounds__(kThreads)
+stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
+              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+{
+    constexpr int NBLK = (B < 8) ? 8 / B : 1;
+    constexpr int LANES = (B < 8) ? 1 : B / 8;
+
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
     if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
 
-    const int64_t n_chunks = (n + 7) >> 3;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    const int64_t wave_first = (int64_t)blockIdx.x * kThreads + (threadIdx.x & ~63);
+    int64_t chunk = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int64_t base = chunk - (threadIdx.x & 63);                  // wave-uniform loop counter
 
-    for (int64_t base = wave_first; base < n_chunks; base += stride) {
-        const int64_t chunk = base + (threadIdx.x & 63);
-        const int64_t first = chunk << 3;
-        const int count = (int)min((int64_t)8, n - first);      // <= 0 past the end
-        float v[8];
-        if (count == 8) load8<DT>(x, first, v);
-        else load_partial<DT>(x, first, count, v);
+    RawChunk<DT> raw{};
+    if (chunk < n_full) raw = load_raw<DT>(x, chunk);
 
-        if (T != 1.0f) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = v[i] / T;        // IEEE division (hierarchical)
-        }
+    for (; base < n_full; base += stride, chunk += stride) {
+        RawChunk<DT> nxt{};
+        if (chunk + stride < n_full) nxt = load_raw<DT>(x, chunk + stride);
 
-        // block abs-max
-        float amax[NBLK];
-#pragma unroll
-        for (int k = 0; k < NBLK; ++k) {
-            float a = 0.0f;
-#pragma unroll
-            for (int i = 0; i < EPB; ++i) a = fmaxf(a, __builtin_fabsf(v[k * EPB + i]));
-            amax[k] = group_max<LANES>(a);
-        }
+        float v[8], sse_sel[4];
+        uint32_t packed, code_out[NBLK];
+        widen<DT>(raw, v);
+        process_chunk<B, FMT, FOUR6, HAS_T>(v, T, pz != 0, tab, packed, code_out, sse_sel);
 
-        uint32_t packed = 0u, code_out[NBLK];
-        float sse_sel[4];
-
-        if constexpr (FMT == kE8M0) {
-            // power-of-two scale: v / 2^k is exact, multiply by 2^-k
-            float sq[8];
-#pragma unroll
-            for (int k = 0; k < NBLK; ++k) {
-                const uint32_t c = pow2_code(amax[k]);
-                code_out[k] = c;
-                const float S = (c == 0u) ? u2f(0x00400000u) : u2f(c << 23);
-                const float Sinv = (c == 254u) ? u2f(0x00400000u) : u2f((254u - c) << 23);
-#pragma unroll
-                for (int i = 0; i < EPB; ++i) {
-                    const int j = k * EPB + i;
-                    const uint32_t mag = e2m1_round_mag(__builtin_fabsf(v[j] * Sinv));
-                    const uint32_t sign = f2u(v[j]) >> 31;
-                    const float q = u2f(f2u(e2m1_mag_value(mag)) | (sign << 31));
-                    const float e = __builtin_fmaf(-q, S, v[j]);
-                    sq[j] = e * e;
-                    packed |= ((sign << 3) | mag) << (4 * j);
+        if (chunk < n_full) {
+            __builtin_nontemporal_store(packed, codes + chunk);
+            if constexpr (B >= 8) {
+                if ((threadIdx.x & (LANES - 1)) == 0) {
+                    const int64_t blk = chunk / LANES;
+                    scales[blk] = (uint8_t)code_out[0];
+                    if (sse_out) sse_out[blk] = sse_sel[0];
                 }
-            }
-            block_sse<B>(sq, sse_sel);
-        } else {
-            // one scale per block inside the lane; gather per-element scale operands
-            uint32_t c6[NBLK], c4[NBLK];
-#pragma unroll
-            for (int k = 0; k < NBLK; ++k) {
-                c6[k] = absmax_code<FMT, 6>(amax[k], pz != 0);
-                if constexpr (FOUR6) c4[k] = absmax_code<FMT, 4>(amax[k], pz != 0);
-            }
-            float sq6[8], sse6[4];
-            quant_lane<NBLK, EPB>(v, c6, tab, packed, sq6);
-            block_sse<B>(sq6, sse6);
-#pragma unroll
-            for (int k = 0; k < NBLK; ++k) { code_out[k] = c6[k]; sse_sel[k] = sse6[k]; }
-
-            if constexpr (FOUR6) {
-                float sq4[8], sse4[4];
-                uint32_t packed4;
-                quant_lane<NBLK, EPB>(v, c4, tab, packed4, sq4);
-                block_sse<B>(sq4, sse4);
-                // Eq. 4: M = 4 only when its SSE is strictly lower
-#pragma unroll
-                for (int k = 0; k < NBLK; ++k) {
-                    if (sse4[k] < sse6[k]) {
-                        constexpr uint32_t m = (EPB == 8) ? 0xFFFFFFFFu : ((1u << (4 * EPB)) - 1u);
-                        const uint32_t mask = m << (4 * EPB * k);
-                        packed = (packed & ~mask) | (packed4 & mask);
-                        code_out[k] = c4[k];
-                        sse_sel[k] = sse4[k];
-                    }
-                }
-            }
-        }
-
-        if (count <= 0) continue;
-        if (count == 8) {
-            codes[chunk] = packed;
-        } else {
-            uint8_t* cb = reinterpret_cast<uint8_t*>(codes) + chunk * 4;
-            for (int i = 0; i < count / 2; ++i) cb[i] = (uint8_t)(packed >> (8 * i));
-        }
-        if constexpr (B >= 8) {
-            if ((threadIdx.x & (LANES - 1)) == 0) {
-                const int64_t blk = chunk / LANES;
-                scales[blk] = (uint8_t)code_out[0];
-                if (sse_out) sse_out[blk] = sse_sel[0];
-            }
-        } else {
-            const int64_t blk0 = chunk * NBLK;
-            const int nvalid = count / B;
-            if (nvalid == NBLK) {
-                if constexpr (NBLK == 2) {
-                    *reinterpret_cast<uint16_t*>(scales + blk0) = (uint16_t)(code_out[0] | (code_out[1] << 8));
-                    if (sse_out) *reinterpret_cast<float2*>(sse_out + blk0) = make_float2(sse_sel[0], sse_sel[1]);
-                } else {
-                    *reinterpret_cast<uint32_t*>(scales + blk0) =
-                        code_out[0] | (code_out[1] << 8) | (code_out[2] << 16) | (code_out[3] << 24);
-                    if (sse_out)
-                        *reinterpret_cast<float4*>(sse_out + blk0) =
-                            make_float4(sse_sel[0], sse_sel[1], sse_sel[2], sse_sel[3]);
-                }
+            } else if constexpr (NBLK == 2) {
+                const int64_t blk0 = chunk * 2;
+                *reinterpret_cast<uint16_t*>(scales + blk0) = (uint16_t)(code_out[0] | (code_out[1] << 8));
+                if (sse_out) *reinterpret_cast<float2*>(sse_out + blk0) = make_float2(sse_sel[0], sse_sel[1]);
             } else {
-                for (int k = 0; k < nvalid; ++k) {
-                    scales[blk0 + k] = (uint8_t)code_out[k];
-                    if (sse_out) sse_out[blk0 + k] = sse_sel[k];
-                }
+                const int64_t blk0 = chunk * 4;
+                *reinterpret_cast<uint32_t*>(scales + blk0) =
+                    code_out[0] | (code_out[1] << 8) | (code_out[2] << 16) | (code_out[3] << 24);
+                if (sse_out)
+                    *reinterpret_cast<float4*>(sse_out + blk0) =
+                        make_float4(sse_sel[0], sse_sel[1], sse_sel[2], sse_sel[3]);
+            }
+        }
+        raw = nxt;
+    }
+}
+
+// Ragged tail: when n is not a multiple of 8 (only possible for b = 2 or 4) the last
+// `count` < 8 elements are handled by lane 0 of one wavefront, reading and writing element-wise.
+template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
+__global__ void __launch_bounds__(64)
+stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T, int pz,
+                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+{
+    constexpr int NBLK = (B < 8) ? 8 / B : 1;
+    __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
+    if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
+
+    float v[8], sse_sel[4];
+    uint32_t packed, code_out[NBLK];
+    load_partial<DT>(x, first, (threadIdx.x == 0) ? count : 0, v);
+    process_chunk<B, FMT, FOUR6, HAS_T>(v, T, pz != 0, tab, packed, code_out, sse_sel);
+    if (threadIdx.x != 0) return;
+    for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
+    if constexpr (B < 8) {
+        for (int k = 0; k < NBLK; ++k) {
+            if (k < count / B) {
+                scales[first / B + k] = (uint8_t)code_out[k];
+                if (sse_out) sse_out[first / B + k] = sse_sel[k];
             }
         }
     }
@@ -226,25 +286,47 @@ stream_kernel(const void* __restrict__ x, int64_t n, float T, int pz,
 
 // ------------------------------------------------------------------------------ dispatch
 
+template <int DT, int B, int FMT, bool FOUR6>
+static hipError_t launch_recipe(const StreamArgs& a, int pz)
+{
+    const int64_t n_full = a.n / 8;
+    const int count = (int)(a.n - n_full * 8);
+    const bool has_t = (a.T != 1.0f);
+    if (n_full > 0) {
+        const dim3 grid(stream_grid(n_full)), block(kThreads);
+        uint32_t* codes = reinterpret_cast<uint32_t*>(a.codes);
+        if (has_t)
+            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, true>), grid, block, 0, a.stream,
+                               a.x, n_full, a.T, pz, codes, a.scales, a.sse);
+        else
+            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, false>), grid, block, 0, a.stream,
+                               a.x, n_full, a.T, pz, codes, a.scales, a.sse);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if constexpr (B < 8) {
+        if (count > 0) {
+            if (has_t)
+                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, true>), dim3(1), dim3(64), 0, a.stream,
+                                   a.x, n_full * 8, count, a.T, pz, a.codes, a.scales, a.sse);
+            else
+                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, false>), dim3(1), dim3(64), 0, a.stream,
+                                   a.x, n_full * 8, count, a.T, pz, a.codes, a.scales, a.sse);
+        }
+    }
+    return hipGetLastError();
+}
+
 template <int DT, int B, int FMT>
 static hipError_t launch_fmt(const StreamArgs& a)
 {
-    const int64_t n_chunks = (a.n + 7) / 8;
-    const int grid = stream_grid(n_chunks);
     const bool four6 = (a.recipe == 2 || a.recipe == 3);
     const int pz = (a.recipe == 1 || a.recipe == 3) ? 1 : 0;
     if constexpr (FMT == kE8M0) {
-        hipLaunchKernelGGL((stream_kernel<DT, B, FMT, false>), dim3(grid), dim3(kThreads), 0, a.stream,
-                           a.x, a.n, a.T, 0, (uint32_t*)a.codes, a.scales, a.sse);
+        return launch_recipe<DT, B, FMT, false>(a, 0);
     } else {
-        if (four6)
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, true>), dim3(grid), dim3(kThreads), 0, a.stream,
-                               a.x, a.n, a.T, pz, (uint32_t*)a.codes, a.scales, a.sse);
-        else
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, false>), dim3(grid), dim3(kThreads), 0, a.stream,
-                               a.x, a.n, a.T, pz, (uint32_t*)a.codes, a.scales, a.sse);
+        return four6 ? launch_recipe<DT, B, FMT, true>(a, pz) : launch_recipe<DT, B, FMT, false>(a, pz);
     }
-    return hipGetLastError();
 }
 
 template <int DT, int B>
