@@ -45,11 +45,18 @@ __device__ __forceinline__ float sf_decode(uint32_t code)
 // finite value.  Normal range: RNE of the fp32 mantissa to 3 bits by the usual
 // add-half-minus-one-plus-lsb on the bit pattern.  Sub-normal range: adding 2^(emin+20)
 // makes the fp32 adder itself round y to a multiple of eps (ties to even).
+//
+// For E4M3 the gfx950 conversion v_cvt_pk_fp8_f32 does the same rounding (OCP E4M3, nearest
+// even, sub-normals included) in one instruction; it turns values beyond 448 into NaN rather
+// than clipping, hence the clamp in front of it.
 template <int FMT>
 __device__ __forceinline__ uint32_t sf_encode_rne(float y)
 {
     constexpr int bias = ScaleFmt<FMT>::kBias;
     y = fminf(y, ScaleFmt<FMT>::kMaxValue);
+    if constexpr (FMT == kE4M3) {
+        return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(y, y, 0, false) & 0xFFu;
+    }
     const uint32_t b = f2u(y);
     const uint32_t nrm = ((b + 0x7FFFFu + ((b >> 20) & 1u)) >> 20) - ((127u - bias) << 3);
     const float magic = u2f((uint32_t)(127 + (1 - bias) + 20) << 23);
@@ -185,14 +192,22 @@ constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each group of 8
 constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each row of 16
 
-template <int LANES>
-__device__ __forceinline__ float group_max(float v)
+// Maximum of non-negative floats: their bit patterns order like unsigned integers.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v)
 {
-    if constexpr (LANES >= 2) v = fmaxf(v, dpp_f<kDppXor1>(v));
-    if constexpr (LANES >= 4) v = fmaxf(v, dpp_f<kDppXor2>(v));
-    if constexpr (LANES >= 8) v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
-    if constexpr (LANES >= 16) v = fmaxf(v, dpp_f<kDppMirror>(v));
-    return v;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+
+template <int LANES>
+__device__ __forceinline__ float group_max(float nonneg)
+{
+    uint32_t v = f2u(nonneg);
+    if constexpr (LANES >= 2) v = max(v, dpp_u<kDppXor1>(v));
+    if constexpr (LANES >= 4) v = max(v, dpp_u<kDppXor2>(v));
+    if constexpr (LANES >= 8) v = max(v, dpp_u<kDppHalfMirror>(v));
+    if constexpr (LANES >= 16) v = max(v, dpp_u<kDppMirror>(v));
+    return u2f(v);
 }
 
 template <int LANES>

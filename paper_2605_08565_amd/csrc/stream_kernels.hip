@@ -10,6 +10,10 @@
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"
 
+#ifndef MXQ_STREAM_ITEMS
+#define MXQ_STREAM_ITEMS 1
+#endif
+
 namespace mxq {
 
 // Eq. 2 / Eq. 3: scale code from the block abs-max for M = 6 or M = 4.
@@ -177,15 +181,16 @@ template <int DT> struct RawChunk;
 template <> struct RawChunk<kBF16> { u32x4 a; };
 template <> struct RawChunk<kF32> { u32x4 a, b; };
 
+// `tile` points at the workgroup's 256 chunks (wave-uniform), `lane` is the chunk inside it.
 template <int DT>
-__device__ __forceinline__ RawChunk<DT> load_raw(const void* x, int64_t chunk)
+__device__ __forceinline__ RawChunk<DT> load_raw(const u32x4* __restrict__ tile, uint32_t lane)
 {
     RawChunk<DT> r;
     if constexpr (DT == kBF16) {
-        r.a = __builtin_nontemporal_load(static_cast<const u32x4*>(x) + chunk);
+        r.a = __builtin_nontemporal_load(tile + lane);
     } else {
-        r.a = __builtin_nontemporal_load(static_cast<const u32x4*>(x) + 2 * chunk);
-        r.b = __builtin_nontemporal_load(static_cast<const u32x4*>(x) + 2 * chunk + 1);
+        r.a = __builtin_nontemporal_load(tile + 2u * lane);
+        r.b = __builtin_nontemporal_load(tile + 2u * lane + 1u);
     }
     return r;
 }
@@ -204,57 +209,136 @@ __device__ __forceinline__ void widen(const RawChunk<DT>& r, float (&v)[8])
     }
 }
 
-// Main kernel: the n_full = n / 8 complete chunks.
+// Results of one lane for one tile, kept in registers until they are stored.
+template <int B>
+struct TileOut {
+    static constexpr int NBLK = (B < 8) ? 8 / B : 1;
+    uint32_t packed;
+    uint32_t code[NBLK];
+    float sse[4];
+};
+
+// Stores of one slice (256 chunks starting at chunk c0, a multiple of 256).  All slice
+// arithmetic is wave-uniform: addresses are a scalar base plus a 32-bit lane offset.
+template <int B>
+__device__ __forceinline__ void store_slice(const TileOut<B>& o, int64_t c0, int64_t n_full,
+                                            uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                                            float* __restrict__ sse_out)
+{
+    constexpr int NBLK = TileOut<B>::NBLK;
+    constexpr int LANES = (B < 8) ? 1 : B / 8;
+    const uint32_t tid = threadIdx.x;
+    if (c0 >= n_full) return;                                        // uniform
+    const uint32_t here = (uint32_t)min((int64_t)kThreads, n_full - c0);
+    if (tid < here) {
+        __builtin_nontemporal_store(o.packed, codes + c0 + tid);
+        if constexpr (B >= 8) {
+            if ((tid & (LANES - 1)) == 0) {
+                const uint32_t blk = tid / LANES;
+                (scales + c0 / LANES)[blk] = (uint8_t)o.code[0];
+                if (sse_out) (sse_out + c0 / LANES)[blk] = o.sse[0];
+            }
+        } else if constexpr (NBLK == 2) {
+            reinterpret_cast<uint16_t*>(scales + c0 * 2)[tid] = (uint16_t)(o.code[0] | (o.code[1] << 8));
+            if (sse_out) reinterpret_cast<float2*>(sse_out + c0 * 2)[tid] = make_float2(o.sse[0], o.sse[1]);
+        } else {
+            reinterpret_cast<uint32_t*>(scales + c0 * 4)[tid] =
+                o.code[0] | (o.code[1] << 8) | (o.code[2] << 16) | (o.code[3] << 24);
+            if (sse_out)
+                reinterpret_cast<float4*>(sse_out + c0 * 4)[tid] =
+                    make_float4(o.sse[0], o.sse[1], o.sse[2], o.sse[3]);
+        }
+    }
+}
+
+// A workgroup tile is kItems slices of 256 chunks; every lane owns one chunk of each slice.
+constexpr int kItems = MXQ_STREAM_ITEMS;
+constexpr int64_t kTileChunks = (int64_t)kThreads * kItems;
+
+template <int DT>
+__device__ __forceinline__ void load_tile(RawChunk<DT> (&buf)[kItems], const void* __restrict__ x,
+                                          int64_t c0, int64_t n_full)
+{
+    constexpr int64_t kVecPerChunk = (DT == kBF16) ? 1 : 2;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t ci = c0 + (int64_t)i * kThreads;
+        if (ci < n_full) {                                           // uniform
+            const uint32_t left = (uint32_t)min((int64_t)kThreads, n_full - ci);
+            buf[i] = load_raw<DT>(static_cast<const u32x4*>(x) + ci * kVecPerChunk,
+                                  min((uint32_t)threadIdx.x, left - 1u));
+        }
+    }
+}
+
+// One step of the software pipeline for the tile at c0 whose raw data sits in `cur`:
+//   wait until `cur` has landed -> issue the stores of the PREVIOUS tile -> issue the loads of
+//   the NEXT tile into `nxt` -> quantise `cur` into `out`.
+// On gfx9 loads and stores share one in-order counter, so the wait at the top covers every
+// memory operation still in flight; with this order all of them were issued a whole compute
+// phase earlier and the wait is short.
+template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
+__device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChunk<DT> (&nxt)[kItems],
+                                            TileOut<B> (&out)[kItems], bool have_prev, int64_t c_prev,
+                                            const void* __restrict__ x, int64_t c0, int64_t stride,
+                                            int64_t n_full, float T, bool pz, const ScaleEntry* tab,
+                                            uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                                            float* __restrict__ sse_out)
+{
+    float v[kItems][8];
+    __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0)
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) widen<DT>(cur[i], v[i]);
+    __builtin_amdgcn_sched_barrier(0);
+    if (have_prev) {                                                 // uniform
+#pragma unroll
+        for (int i = 0; i < kItems; ++i)
+            store_slice<B>(out[i], c_prev + (int64_t)i * kThreads, n_full, codes, scales, sse_out);
+    }
+    if (c0 + stride < n_full) load_tile<DT>(nxt, x, c0 + stride, n_full);      // uniform
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+        process_chunk<B, FMT, FOUR6, HAS_T>(v[i], T, pz, tab, out[i].packed, out[i].code, out[i].sse);
+}
+
+// Main kernel: the n_full = n / 8 complete chunks, grid-stride over workgroup tiles with two
+// register buffers alternating between "being processed" and "in flight".
 template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
 __global__ void __launch_bounds__(kThreads)
 stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
               uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
-    constexpr int NBLK = (B < 8) ? 8 / B : 1;
-    constexpr int LANES = (B < 8) ? 1 : B / 8;
-
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
     if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
 
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    int64_t chunk = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    int64_t base = chunk - (threadIdx.x & 63);                  // wave-uniform loop counter
+    const int64_t stride = (int64_t)gridDim.x * kTileChunks;
+    int64_t c0 = (int64_t)blockIdx.x * kTileChunks;
+    if (c0 >= n_full) return;
 
-    RawChunk<DT> raw{};
-    if (chunk < n_full) raw = load_raw<DT>(x, chunk);
-
-    for (; base < n_full; base += stride, chunk += stride) {
-        RawChunk<DT> nxt{};
-        if (chunk + stride < n_full) nxt = load_raw<DT>(x, chunk + stride);
-
-        float v[8], sse_sel[4];
-        uint32_t packed, code_out[NBLK];
-        widen<DT>(raw, v);
-        process_chunk<B, FMT, FOUR6, HAS_T>(v, T, pz != 0, tab, packed, code_out, sse_sel);
-
-        if (chunk < n_full) {
-            __builtin_nontemporal_store(packed, codes + chunk);
-            if constexpr (B >= 8) {
-                if ((threadIdx.x & (LANES - 1)) == 0) {
-                    const int64_t blk = chunk / LANES;
-                    scales[blk] = (uint8_t)code_out[0];
-                    if (sse_out) sse_out[blk] = sse_sel[0];
-                }
-            } else if constexpr (NBLK == 2) {
-                const int64_t blk0 = chunk * 2;
-                *reinterpret_cast<uint16_t*>(scales + blk0) = (uint16_t)(code_out[0] | (code_out[1] << 8));
-                if (sse_out) *reinterpret_cast<float2*>(sse_out + blk0) = make_float2(sse_sel[0], sse_sel[1]);
-            } else {
-                const int64_t blk0 = chunk * 4;
-                *reinterpret_cast<uint32_t*>(scales + blk0) =
-                    code_out[0] | (code_out[1] << 8) | (code_out[2] << 16) | (code_out[3] << 24);
-                if (sse_out)
-                    *reinterpret_cast<float4*>(sse_out + blk0) =
-                        make_float4(sse_sel[0], sse_sel[1], sse_sel[2], sse_sel[3]);
-            }
-        }
-        raw = nxt;
+    RawChunk<DT> bufA[kItems], bufB[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) { bufA[i] = RawChunk<DT>{}; bufB[i] = RawChunk<DT>{}; }
+    load_tile<DT>(bufA, x, c0, n_full);
+    TileOut<B> out[kItems];
+    bool have_prev = false;
+    int64_t c_prev = c0;
+    while (true) {
+        stream_step<DT, B, FMT, FOUR6, HAS_T>(bufA, bufB, out, have_prev, c_prev, x, c0, stride, n_full,
+                                              T, pz != 0, tab, codes, scales, sse_out);
+        have_prev = true;
+        c_prev = c0;
+        c0 += stride;
+        if (c0 >= n_full) break;
+        stream_step<DT, B, FMT, FOUR6, HAS_T>(bufB, bufA, out, true, c_prev, x, c0, stride, n_full,
+                                              T, pz != 0, tab, codes, scales, sse_out);
+        c_prev = c0;
+        c0 += stride;
+        if (c0 >= n_full) break;
     }
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+        store_slice<B>(out[i], c_prev + (int64_t)i * kThreads, n_full, codes, scales, sse_out);
 }
 
 // Ragged tail: when n is not a multiple of 8 (only possible for b = 2 or 4) the last
@@ -293,7 +377,7 @@ static hipError_t launch_recipe(const StreamArgs& a, int pz)
     const int count = (int)(a.n - n_full * 8);
     const bool has_t = (a.T != 1.0f);
     if (n_full > 0) {
-        const dim3 grid(stream_grid(n_full)), block(kThreads);
+        const dim3 grid(stream_grid((n_full + kItems - 1) / kItems)), block(kThreads);
         uint32_t* codes = reinterpret_cast<uint32_t*>(a.codes);
         if (has_t)
             hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, true>), grid, block, 0, a.stream,
