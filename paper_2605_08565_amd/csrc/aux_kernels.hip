@@ -16,77 +16,100 @@ __device__ __forceinline__ float scale_value_any(int fmt, uint32_t code)
     return (code > (uint32_t)ScaleFmt<kUE5M3>::kMaxCode) ? nan : sf_decode<kUE5M3>(code);
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+using bf16x2 = __bf16 __attribute__((ext_vector_type(2)));
+
+// Two fp32 -> two bf16 (round to nearest even, v_cvt_pk_bf16_f32), first value in the low half.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    const uint32_t u = f2u(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;       // keep NaN a NaN
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// One lane = 8 consecutive elements = one dword of codes.
-template <int DT>
+// One lane = 8 consecutive elements = one dword of codes; a block of b >= 8 elements spans
+// b/8 lanes that all read the same scale byte, a block of b < 8 lies inside the lane.
+template <int DT, int B>
 __global__ void __launch_bounds__(kThreads)
 dequant_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
-               int block_shift, int fmt, float T, void* __restrict__ out)
+               int fmt, float T, void* __restrict__ out)
 {
+    constexpr int NBLK = (B < 8) ? 8 / B : 1;
+    constexpr int LANES = (B < 8) ? 1 : B / 8;
+    constexpr int EPB = (B < 8) ? B : 8;
     const int64_t n_chunks = (n + 7) >> 3;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t chunk = (int64_t)blockIdx.x * kThreads + threadIdx.x; chunk < n_chunks; chunk += stride) {
+    for (int64_t c0 = (int64_t)blockIdx.x * kThreads; c0 < n_chunks; c0 += stride) {     // uniform
+        const uint32_t tid = threadIdx.x;
+        if (tid >= (uint32_t)min((int64_t)kThreads, n_chunks - c0)) continue;
+        const int64_t chunk = c0 + tid;
         const int64_t first = chunk << 3;
         const int count = (int)min((int64_t)8, n - first);
         uint32_t packed = 0u;
         if (count == 8) {
-            packed = codes[chunk];
+            packed = __builtin_nontemporal_load(codes + chunk);
         } else {
             const uint8_t* cb = reinterpret_cast<const uint8_t*>(codes) + chunk * 4;
             for (int i = 0; i < count / 2; ++i) packed |= (uint32_t)cb[i] << (8 * i);
         }
-        float r[8];
+        float S[NBLK];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float val = 0.0f;
-            if (i < count) {
-                const uint32_t c = (packed >> (4 * i)) & 0xFu;
-                const float S = scale_value_any(fmt, scales[(first + i) >> block_shift]);
-                const float q = u2f(f2u(e2m1_mag_value(c & 7u)) | ((c & 8u) << 28));
-                val = (q * S) * T;
-            }
-            r[i] = val;
+        for (int k = 0; k < NBLK; ++k) {
+            const int64_t blk = (B >= 8) ? chunk / LANES : chunk * NBLK + k;
+            S[k] = (B >= 8 || k < count / B) ? scale_value_any(fmt, scales[blk]) : 0.0f;
         }
+        float r[8];
+        e2m1_unpack8(packed, 1.0f, r);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = (r[i] * S[i / EPB]) * T;
         if (count == 8) {
             if constexpr (DT == kBF16) {
-                uint4 o;
-                o.x = f32_to_bf16_rne(r[0]) | (f32_to_bf16_rne(r[1]) << 16);
-                o.y = f32_to_bf16_rne(r[2]) | (f32_to_bf16_rne(r[3]) << 16);
-                o.z = f32_to_bf16_rne(r[4]) | (f32_to_bf16_rne(r[5]) << 16);
-                o.w = f32_to_bf16_rne(r[6]) | (f32_to_bf16_rne(r[7]) << 16);
-                *reinterpret_cast<uint4*>(static_cast<uint16_t*>(out) + first) = o;
+                u32x4 o;
+                o.x = pack_bf16x2(r[0], r[1]);
+                o.y = pack_bf16x2(r[2], r[3]);
+                o.z = pack_bf16x2(r[4], r[5]);
+                o.w = pack_bf16x2(r[6], r[7]);
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(out) + first));
             } else {
-                float4* p = reinterpret_cast<float4*>(static_cast<float*>(out) + first);
-                p[0] = make_float4(r[0], r[1], r[2], r[3]);
-                p[1] = make_float4(r[4], r[5], r[6], r[7]);
+                u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(out) + first);
+                const u32x4 lo = {f2u(r[0]), f2u(r[1]), f2u(r[2]), f2u(r[3])};
+                const u32x4 hi = {f2u(r[4]), f2u(r[5]), f2u(r[6]), f2u(r[7])};
+                __builtin_nontemporal_store(lo, p);
+                __builtin_nontemporal_store(hi, p + 1);
             }
         } else {
             for (int i = 0; i < count; ++i) {
-                if constexpr (DT == kBF16) static_cast<uint16_t*>(out)[first + i] = (uint16_t)f32_to_bf16_rne(r[i]);
-                else static_cast<float*>(out)[first + i] = r[i];
+                if constexpr (DT == kBF16)
+                    static_cast<uint16_t*>(out)[first + i] = (uint16_t)(pack_bf16x2(r[i], 0.0f) & 0xFFFFu);
+                else
+                    static_cast<float*>(out)[first + i] = r[i];
             }
         }
     }
+}
+
+template <int DT>
+static void launch_dequant_dt(const DequantArgs& a, int grid)
+{
+#define MXQ_DQ(BB)                                                                                   \
+    hipLaunchKernelGGL((dequant_kernel<DT, BB>), dim3(grid), dim3(kThreads), 0, a.stream,           \
+                       (const uint32_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, a.out)
+    switch (a.block) {
+        case 2: MXQ_DQ(2); break;
+        case 4: MXQ_DQ(4); break;
+        case 8: MXQ_DQ(8); break;
+        case 16: MXQ_DQ(16); break;
+        case 32: MXQ_DQ(32); break;
+        case 64: MXQ_DQ(64); break;
+        default: MXQ_DQ(128); break;
+    }
+#undef MXQ_DQ
 }
 
 hipError_t launch_dequant(const DequantArgs& a)
 {
     const int64_t n_chunks = (a.n + 7) / 8;
     const int grid = stream_grid(n_chunks);
-    int shift = 0;
-    while ((1 << shift) < a.block) ++shift;
-    if (a.dtype == kBF16)
-        hipLaunchKernelGGL((dequant_kernel<kBF16>), dim3(grid), dim3(kThreads), 0, a.stream,
-                           (const uint32_t*)a.codes, a.scales, a.n, shift, a.scale_fmt, a.T, a.out);
-    else
-        hipLaunchKernelGGL((dequant_kernel<kF32>), dim3(grid), dim3(kThreads), 0, a.stream,
-                           (const uint32_t*)a.codes, a.scales, a.n, shift, a.scale_fmt, a.T, a.out);
+    if (a.dtype == kBF16) launch_dequant_dt<kBF16>(a, grid);
+    else launch_dequant_dt<kF32>(a, grid);
     return hipGetLastError();
 }
 
@@ -96,21 +119,53 @@ hipError_t launch_dequant(const DequantArgs& a)
 // captured in a graph).
 __global__ void absmax_clear_kernel(uint32_t* out) { *out = 0u; }
 
+// Each workgroup walks tiles of 4 x 256 chunks with four independent 128-bit loads per lane in
+// flight; the ragged last chunk (n not a multiple of 8) is read element-wise by one lane.
+constexpr int kAbsItems = 4;
+
 template <int DT>
 __global__ void __launch_bounds__(kThreads)
 absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out)
 {
-    const int64_t n_chunks = (n + 7) >> 3;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    constexpr int64_t kVec = (DT == kBF16) ? 1 : 2;               // 128-bit vectors per chunk
+    const int64_t n_vec = (n >> 3) * kVec;                         // complete vectors
+    const int64_t tile = (int64_t)kThreads * kAbsItems;
+    const int64_t stride = (int64_t)gridDim.x * tile;
+    const u32x4* xv = static_cast<const u32x4*>(x);
     uint32_t m = 0u;
-    for (int64_t chunk = (int64_t)blockIdx.x * kThreads + threadIdx.x; chunk < n_chunks; chunk += stride) {
-        const int64_t first = chunk << 3;
-        const int count = (int)min((int64_t)8, n - first);
-        float v[8];
-        if (count == 8) load8<DT>(x, first, v);
-        else load_partial<DT>(x, first, count, v);
+    for (int64_t v0 = (int64_t)blockIdx.x * tile; v0 < n_vec; v0 += stride) {            // uniform
+        u32x4 r[kAbsItems];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) m = max(m, f2u(v[i]) & 0x7FFFFFFFu);
+        for (int i = 0; i < kAbsItems; ++i) {
+            const int64_t vi = v0 + (int64_t)i * kThreads;
+            r[i] = u32x4{0u, 0u, 0u, 0u};
+            if (vi < n_vec) {                                                               // uniform
+                const uint32_t left = (uint32_t)min((int64_t)kThreads, n_vec - vi);
+                r[i] = __builtin_nontemporal_load(xv + vi + min((uint32_t)threadIdx.x, left - 1u));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kAbsItems; ++i) {
+            if constexpr (DT == kBF16) {
+                // two bf16 per dword: compare the high halves and the low halves separately
+                const uint32_t hi = max(max(r[i].x & 0x7FFF0000u, r[i].y & 0x7FFF0000u),
+                                        max(r[i].z & 0x7FFF0000u, r[i].w & 0x7FFF0000u));
+                const uint32_t lo = max(max(r[i].x & 0x7FFFu, r[i].y & 0x7FFFu),
+                                        max(r[i].z & 0x7FFFu, r[i].w & 0x7FFFu));
+                m = max(m, max(hi, lo << 16));
+            } else {
+                m = max(m, max(max(r[i].x & 0x7FFFFFFFu, r[i].y & 0x7FFFFFFFu),
+                               max(r[i].z & 0x7FFFFFFFu, r[i].w & 0x7FFFFFFFu)));
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        for (int64_t i = (n >> 3) << 3; i < n; ++i) {
+            uint32_t b;
+            if constexpr (DT == kBF16) b = (uint32_t)static_cast<const uint16_t*>(x)[i] << 16;
+            else b = static_cast<const uint32_t*>(x)[i];
+            m = max(m, b & 0x7FFFFFFFu);
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
@@ -129,8 +184,11 @@ hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, hipStr
     hipLaunchKernelGGL(absmax_clear_kernel, dim3(1), dim3(1), 0, stream, (uint32_t*)out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
-    const int64_t n_chunks = (n + 7) / 8;
-    const int grid = stream_grid(n_chunks);
+    // one workgroup per 1024 chunks, at most two workgroups per compute unit: few enough that
+    // the closing atomic max (one per workgroup, all on one word) stays cheap
+    const int64_t n_tiles = ((n + 7) / 8 + kThreads * kAbsItems - 1) / (kThreads * kAbsItems);
+    const int64_t capw = 512;
+    const int grid = (int)(n_tiles < 1 ? 1 : (n_tiles < capw ? n_tiles : capw));
     if (dtype == kBF16)
         hipLaunchKernelGGL((absmax_kernel<kBF16>), dim3(grid), dim3(kThreads), 0, stream, x, n, (uint32_t*)out);
     else

@@ -17,11 +17,13 @@ namespace mxq {
 
 // hi/lo split of 1/m for m = 1 + i/8 (see "Quotients whose rounding decisions are exact").
 __device__ constexpr float mant_value(int i) { return 1.0f + (float)i * 0.125f; }
-__device__ constexpr float mant_rhi(int i) { return (float)(1.0 / (1.0 + i * 0.125)); }
-__device__ constexpr float mant_rlo(int i)
+__device__ constexpr float mant_rhi(int i)                          // 1/m rounded toward zero
 {
-    return (float)(1.0 / (1.0 + i * 0.125) - (double)(float)(1.0 / (1.0 + i * 0.125)));
+    const double d = 1.0 / (1.0 + i * 0.125);
+    const float r = (float)d;
+    return ((double)r > d) ? __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, r) - 1u) : r;
 }
+__device__ constexpr float mant_rlo(int i) { return (float)(1.0 / (1.0 + i * 0.125) - (double)mant_rhi(i)); }
 
 template <int B>
 struct BruteState {

@@ -75,18 +75,21 @@ __device__ __forceinline__ uint32_t sf_encode_rne(float y)
 //     fl32(v / d) <, =, > t   <=>   v <, =, > t*d,
 // because v != t*d implies |v/(t*d) - 1| >= 2^-24, which is more than half an ulp of t away.
 // The same holds for  y = fl32(v*r_hi + fl32(v*r_lo))  with r_hi + r_lo = 1/d to 2^-47
-// relative: y is within 2^-46 relative of v/d before its single rounding, far inside the
-// 2^-28 margin the inequality above leaves.  So y may stand in for the IEEE quotient
+// relative (r_hi need not be the nearest float for that): y is within 2^-46 relative of v/d
+// before its single rounding, far inside the 2^-28 margin the inequality above leaves.  So y may stand in for the IEEE quotient
 // wherever only the rounded code is needed.  (The residual v - q*S is computed from v, q and
 // S, never from y.)
 // ---------------------------------------------------------------------------------------
 struct Recip { float hi, lo; };
 
-// r_hi = fl32(1/d) (IEEE division), r_lo = fl32(rho * r_hi) with rho = 1 - r_hi*d exact (fma).
+// r_hi = 1/d rounded toward zero, r_lo = fl32(rho * r_hi) >= 0 with rho = 1 - r_hi*d exact (fma).
+// Both parts are non-negative, so both products in quot() carry the sign of v and a zero
+// quotient (v = -0, or an underflowing product) keeps the sign bit of v.
 __device__ __forceinline__ Recip make_recip(float d)
 {
     Recip r;
     r.hi = 1.0f / d;
+    if (__builtin_fmaf(-r.hi, d, 1.0f) < 0.0f) r.hi = u2f(f2u(r.hi) - 1u);      // was rounded up
     const float rho = __builtin_fmaf(-r.hi, d, 1.0f);
     r.lo = rho * r.hi;
     return r;

@@ -120,9 +120,41 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
     }
 }
 
+// Hierarchical scaling divides every input by the per-tensor scale T in IEEE fp32.  T is the
+// same for the whole tensor, so its correctly rounded reciprocal r is formed once and each
+// quotient is refined twice:
+//     q0 = v*r;  q1 = q0 + r*(v - q0*T);  q2 = q1 + r*(v - q1*T)        (remainders by FMA)
+// q1 is within one ulp of v/T, the FMA remainder of such a quotient is exact, and one more
+// step with a correctly rounded reciprocal then yields the correctly rounded quotient
+// (Markstein's division theorem); the sign of v is copied so that -0 stays -0.  The argument
+// needs intermediate results free of overflow and underflow: the host takes this path only
+// for 2^-20 <= T <= 2^20, and a block whose adjusted abs-max leaves [2^-40, 2^90] (zero
+// excepted) sends its whole wavefront through the plain division instead.
+enum : int { kNoT = 0, kFastT = 1, kSlowT = 2 };
+
+__device__ __forceinline__ float div_by_T(float v, float T, float rT)
+{
+    const float q0 = v * rT;
+    const float q1 = __builtin_fmaf(__builtin_fmaf(-q0, T, v), rT, q0);
+    const float q2 = __builtin_fmaf(__builtin_fmaf(-q1, T, v), rT, q1);
+    return u2f((f2u(q2) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
+}
+
+template <int NBLK, int EPB, int LANES>
+__device__ __forceinline__ void block_amax(const float (&v)[8], float (&amax)[NBLK])
+{
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) a = fmaxf(a, __builtin_fabsf(v[k * EPB + i]));
+        amax[k] = group_max<LANES>(a);
+    }
+}
+
 // Everything between the load and the store for one lane's 8 values.
-template <int B, int FMT, bool FOUR6, bool HAS_T>
-__device__ __forceinline__ void process_chunk(float (&v)[8], float T, bool pz, const ScaleEntry* tab,
+template <int B, int FMT, bool FOUR6, int TMODE>
+__device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, bool pz, const ScaleEntry* tab,
                                               uint32_t& packed, uint32_t (&code_out)[(B < 8) ? 8 / B : 1],
                                               float (&sse_sel)[4])
 {
@@ -130,18 +162,27 @@ __device__ __forceinline__ void process_chunk(float (&v)[8], float T, bool pz, c
     constexpr int LANES = (B < 8) ? 1 : B / 8;         // lanes per block
     constexpr int EPB = (B < 8) ? B : 8;               // elements of one block inside a lane
 
-    if constexpr (HAS_T) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = v[i] / T;            // IEEE division (hierarchical)
-    }
-
     float amax[NBLK];
+    if constexpr (TMODE == kSlowT) {
 #pragma unroll
-    for (int k = 0; k < NBLK; ++k) {
-        float a = 0.0f;
+        for (int i = 0; i < 8; ++i) v[i] = v[i] / T;            // IEEE division
+        block_amax<NBLK, EPB, LANES>(v, amax);
+    } else if constexpr (TMODE == kFastT) {
+        float raw[8];
 #pragma unroll
-        for (int i = 0; i < EPB; ++i) a = fmaxf(a, __builtin_fabsf(v[k * EPB + i]));
-        amax[k] = group_max<LANES>(a);
+        for (int i = 0; i < 8; ++i) { raw[i] = v[i]; v[i] = div_by_T(raw[i], T, rT); }
+        block_amax<NBLK, EPB, LANES>(v, amax);
+        bool unsafe = false;
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k)                  // 0 < amax < 2^-40  or  amax > 2^90
+            unsafe |= (f2u(amax[k]) - 0x2B800000u) > (0x6C800000u - 0x2B800000u) && f2u(amax[k]) != 0u;
+        if (__builtin_amdgcn_ballot_w64(unsafe) != 0ull) {       // rare, wave-uniform
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = raw[i] / T;
+            block_amax<NBLK, EPB, LANES>(v, amax);
+        }
+    } else {
+        block_amax<NBLK, EPB, LANES>(v, amax);
     }
 
     float sq[8];
@@ -277,11 +318,11 @@ __device__ __forceinline__ void load_tile(RawChunk<DT> (&buf)[kItems], const voi
 // On gfx9 loads and stores share one in-order counter, so the wait at the top covers every
 // memory operation still in flight; with this order all of them were issued a whole compute
 // phase earlier and the wait is short.
-template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
+template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChunk<DT> (&nxt)[kItems],
                                             TileOut<B> (&out)[kItems], bool have_prev, int64_t c_prev,
                                             const void* __restrict__ x, int64_t c0, int64_t stride,
-                                            int64_t n_full, float T, bool pz, const ScaleEntry* tab,
+                                            int64_t n_full, float T, float rT, bool pz, const ScaleEntry* tab,
                                             uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
                                             float* __restrict__ sse_out)
 {
@@ -299,12 +340,12 @@ __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChun
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kItems; ++i)
-        process_chunk<B, FMT, FOUR6, HAS_T>(v[i], T, pz, tab, out[i].packed, out[i].code, out[i].sse);
+        process_chunk<B, FMT, FOUR6, TMODE>(v[i], T, rT, pz, tab, out[i].packed, out[i].code, out[i].sse);
 }
 
 // Main kernel: the n_full = n / 8 complete chunks, grid-stride over workgroup tiles with two
 // register buffers alternating between "being processed" and "in flight".
-template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
+template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __global__ void __launch_bounds__(kThreads)
 stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
               uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
@@ -315,6 +356,7 @@ stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
     const int64_t stride = (int64_t)gridDim.x * kTileChunks;
     int64_t c0 = (int64_t)blockIdx.x * kTileChunks;
     if (c0 >= n_full) return;
+    const float rT = 1.0f / T;                                       // correctly rounded
 
     RawChunk<DT> bufA[kItems], bufB[kItems];
 #pragma unroll
@@ -324,14 +366,14 @@ stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
     bool have_prev = false;
     int64_t c_prev = c0;
     while (true) {
-        stream_step<DT, B, FMT, FOUR6, HAS_T>(bufA, bufB, out, have_prev, c_prev, x, c0, stride, n_full,
-                                              T, pz != 0, tab, codes, scales, sse_out);
+        stream_step<DT, B, FMT, FOUR6, TMODE>(bufA, bufB, out, have_prev, c_prev, x, c0, stride, n_full,
+                                              T, rT, pz != 0, tab, codes, scales, sse_out);
         have_prev = true;
         c_prev = c0;
         c0 += stride;
         if (c0 >= n_full) break;
-        stream_step<DT, B, FMT, FOUR6, HAS_T>(bufB, bufA, out, true, c_prev, x, c0, stride, n_full,
-                                              T, pz != 0, tab, codes, scales, sse_out);
+        stream_step<DT, B, FMT, FOUR6, TMODE>(bufB, bufA, out, true, c_prev, x, c0, stride, n_full,
+                                              T, rT, pz != 0, tab, codes, scales, sse_out);
         c_prev = c0;
         c0 += stride;
         if (c0 >= n_full) break;
@@ -343,7 +385,7 @@ stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
 
 // Ragged tail: when n is not a multiple of 8 (only possible for b = 2 or 4) the last
 // `count` < 8 elements are handled by lane 0 of one wavefront, reading and writing element-wise.
-template <int DT, int B, int FMT, bool FOUR6, bool HAS_T>
+template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __global__ void __launch_bounds__(64)
 stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T, int pz,
                    uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
@@ -355,7 +397,7 @@ stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T
     float v[8], sse_sel[4];
     uint32_t packed, code_out[NBLK];
     load_partial<DT>(x, first, (threadIdx.x == 0) ? count : 0, v);
-    process_chunk<B, FMT, FOUR6, HAS_T>(v, T, pz != 0, tab, packed, code_out, sse_sel);
+    process_chunk<B, FMT, FOUR6, TMODE>(v, T, 1.0f / T, pz != 0, tab, packed, code_out, sse_sel);
     if (threadIdx.x != 0) return;
     for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
     if constexpr (B < 8) {
@@ -375,26 +417,34 @@ static hipError_t launch_recipe(const StreamArgs& a, int pz)
 {
     const int64_t n_full = a.n / 8;
     const int count = (int)(a.n - n_full * 8);
-    const bool has_t = (a.T != 1.0f);
+    // reciprocal-refined division only where its exactness argument holds
+    uint32_t tb;
+    static_assert(sizeof(tb) == sizeof(a.T), "");
+    __builtin_memcpy(&tb, &a.T, 4);
+    const bool fast_t = a.T >= 0x1p-20f && a.T <= 0x1p20f && (tb & 0x7FFFFFu) != 0x7FFFFFu;
+    const int tmode = (a.T == 1.0f) ? kNoT : (fast_t ? kFastT : kSlowT);
     if (n_full > 0) {
         const dim3 grid(stream_grid((n_full + kItems - 1) / kItems)), block(kThreads);
         uint32_t* codes = reinterpret_cast<uint32_t*>(a.codes);
-        if (has_t)
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, true>), grid, block, 0, a.stream,
+        if (tmode == kNoT)
+            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kNoT>), grid, block, 0, a.stream,
+                               a.x, n_full, a.T, pz, codes, a.scales, a.sse);
+        else if (tmode == kFastT)
+            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kFastT>), grid, block, 0, a.stream,
                                a.x, n_full, a.T, pz, codes, a.scales, a.sse);
         else
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, false>), grid, block, 0, a.stream,
+            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kSlowT>), grid, block, 0, a.stream,
                                a.x, n_full, a.T, pz, codes, a.scales, a.sse);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if constexpr (B < 8) {
         if (count > 0) {
-            if (has_t)
-                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, true>), dim3(1), dim3(64), 0, a.stream,
+            if (tmode != kNoT)
+                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, kSlowT>), dim3(1), dim3(64), 0, a.stream,
                                    a.x, n_full * 8, count, a.T, pz, a.codes, a.scales, a.sse);
             else
-                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, false>), dim3(1), dim3(64), 0, a.stream,
+                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, kNoT>), dim3(1), dim3(64), 0, a.stream,
                                    a.x, n_full * 8, count, a.T, pz, a.codes, a.scales, a.sse);
         }
     }

@@ -88,6 +88,27 @@ def test_hierarchical_small(oracle, mxq, block):
           tag="hierarchical-f32")
 
 
+def test_hierarchical_division_paths(oracle, mxq):
+    """The per-tensor division has a reciprocal-refined path (2^-20 <= T <= 2^20), a per-wavefront
+    fall-back for blocks of very small or very large adjusted values, and a plain-division path
+    for every other T; all must give the IEEE quotient."""
+    rng = np.random.default_rng(55)
+    x = (rng.standard_normal((24, 512)) * 0.3).astype(np.float32)
+    x[2] *= 1e-30          # adjusted abs-max far below 2^-40: fall-back
+    x[3] *= 1e-38          # sub-normal inputs
+    x[5] *= 1e30           # adjusted abs-max above 2^90 for small T: fall-back (stays finite)
+    x[7, ::3] = 0.0
+    x[8] = 0.0
+    x[9, 1::2] = -0.0
+    all_ones = float(np.float32(1.99999988) * np.float32(0.0625))     # mantissa 0x7FFFFF
+    for T in (0.0917, 3.0e-7, 2.0 ** 21, 2.0 ** -20, 2.0 ** 20, all_ones, 1.0000001, 7.5e-4):
+        for block, fmt, rec in [(16, 1, 0), (4, 1, 2), (64, 2, 3), (32, 0, 0), (8, 1, 4), (2, 2, 1)]:
+            check(oracle, mxq, x, block, fmt, rec, T=T, tag="division-paths")
+    xb = W.f32_to_bf16_bits(x)
+    for T in (0.0917, 3.0e-7):
+        check(oracle, mxq, xb, 16, 1, 2, T=T, tag="division-paths-bf16")
+
+
 def test_config1_full(oracle, mxq):
     """fp32 1024 x 4096, N(0,1), E2M1, block 16, unsigned E4M3, abs-max: the whole tensor."""
     x = W.config1()
