@@ -3,13 +3,13 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
-One *step* is one pass of the whole hot path over the bf16 4096 x 14336 Student-t weight
-matrix (the LLM MLP up-projection shape): every streaming recipe at every block size of that
-configuration, hierarchical scaling (tensor abs-max + quantise with the per-tensor scale), the
-power-of-two and UE5M3 scale formats, the brute-force scale search (E4M3 and UE5M3, block 16
-and 4) and one de-quantise.  Inputs are resident in HBM before the timed region; launches
-rotate over several copies of the input and of the output buffers so that no launch finds
-its data in the 256 MB Infinity Cache.
+One *step* is one pass of the whole hot path over a batch of eight bf16 4096 x 14336 Student-t
+weight matrices (the LLM MLP up-projection shape): every streaming recipe at every block size
+of that configuration, hierarchical scaling (tensor abs-max + quantise with the per-tensor
+scale), the power-of-two and UE5M3 scale formats, the brute-force scale search (E4M3 and UE5M3,
+block 16 and 4) and one de-quantise.  Inputs are resident in HBM before the timed region; each
+pass type runs over the eight matrices back to back, so no launch finds its data in the 256 MB
+Infinity Cache and one event pair brackets eight launches of the same kernel.
 
 Prints ONE JSON line: whole-step throughput in GElem/s (element-passes quantised per second),
 a per-recipe breakdown, the roofline of the kernel that dominates the step (measured with
@@ -32,7 +32,7 @@ ROWS, COLS = 4096, 14336
 N_ELEM = ROWS * COLS
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector (packed FMA) peak
-N_SETS = 8                       # rotating buffer sets (8 x ~150-260 MB of traffic each)
+N_SETS = 8                       # matrices in the batch (each launch moves 150-260 MB)
 
 E8M0, E4M3, UE5M3 = 0, 1, 2
 ABSMAX, ABSMAX_PZ, FOUR6, FOUR6_PZ, BRUTE = 0, 1, 2, 3, 4
@@ -68,6 +68,32 @@ def algorithmic_bytes(kind, block, in_bytes=2):
     return N_ELEM * (in_bytes + 0.5 + 5.0 / block)
 
 
+KERNEL_OF_PASS = {   # pass name -> kernel instantiation, as rocprofv3 prints it
+    "absmax_e4m3_b16": "mxq::stream_kernel<0, 16, 1, false, 0>",
+    "absmax_pz_e4m3_b16": "mxq::stream_kernel<0, 16, 1, false, 0>",
+    "4over6_e4m3_b16": "mxq::stream_kernel<0, 16, 1, true, 0>",
+    "absmax_e4m3_b16_H": "mxq::stream_kernel<0, 16, 1, false, 1>",
+    "brute_e4m3_b16": "mxq::brute_kernel<0, 16, 1, false>",
+    "brute_ue5m3_b16": "mxq::brute_kernel<0, 16, 2, false>",
+    "dequantize_e4m3_b16_bf16": "mxq::dequant_kernel<0, 16>",
+    "tensor_absmax": "mxq::absmax_kernel<0>",
+}
+
+
+def measured_traffic(pass_name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a plain copy of known size); None if that kernel is not in it."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_bf16_4096x14336.md")
+    kern = KERNEL_OF_PASS.get(pass_name)
+    if kern is None or not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) > 7 and cells[1] == f"`{kern}`":
+            return round(float(cells[6]) * 1e6)
+    return None
+
+
 def cpu_baseline(x_np, passes, T, rows):
     """The oracle, as it stands, on the first `rows` rows of the same tensor, same pass list."""
     import numpy as np
@@ -97,8 +123,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--cpu-rows", type=int, default=384, help="rows of the oracle's timed sample")
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of the oracle's timed sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--only", type=str, default="", help="comma-separated pass names (profiling aid)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device copies of one matrix (known size) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -114,44 +143,55 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    # The batch: N_SETS weight matrices.  Matrix 0 is the seeded tensor; the others are row
+    # rotations of it (same distribution, distinct addresses), which keeps start-up short.
     x_np = W.config2()
     x0 = mxq.from_bits(x_np)
-    xs = [x0] + [x0.clone() for _ in range(N_SETS - 1)]
+    xs = [x0] + [torch.roll(x0, shifts=37 * k, dims=0).contiguous() for k in range(1, N_SETS)]
     nb_max = N_ELEM // 4
     outs = [(torch.empty((ROWS, COLS // 2), dtype=torch.uint8, device=dev),
              torch.empty(nb_max, dtype=torch.uint8, device=dev),
              torch.empty(nb_max, dtype=torch.float32, device=dev)) for _ in range(N_SETS)]
-    deq = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device=dev) for _ in range(2)]
-    amax_buf = torch.empty(1, dtype=torch.float32, device=dev)
+    deq = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device=dev) for _ in range(N_SETS)]
+    amax_buf = torch.empty(N_SETS, dtype=torch.float32, device=dev)
 
     A = float(mxq.tensor_absmax(x0).cpu()[0])
     T = mxq.tensor_scale_from_absmax(A, E4M3)
     passes = pass_list()
+    if args.only:
+        keep = set(args.only.split(","))
+        passes = [p for p in passes if p[1] in keep]
     n_quant = sum(1 for p in passes if p[0] == "quant")
 
-    # a valid (codes, scales) pair for the de-quantise pass
-    dq_codes, dq_scales, _ = mxq.quantize(x0, 16, E4M3, ABSMAX)
+    # a valid (codes, scales) pair per matrix for the de-quantise pass
+    dq = [mxq.quantize(x, 16, E4M3, ABSMAX)[:2] for x in xs]
     torch.cuda.synchronize()
 
-    counter = [0]
-
-    def launch(p):
+    def launch(p, k):
         kind, name, b, fmt, rec, hier = p
-        k = counter[0] % N_SETS
-        counter[0] += 1
         if kind == "quant":
             c, s, e = outs[k]
             nb = N_ELEM // b
             mxq.quantize(xs[k], b, fmt, rec, tensor_scale=T if hier else 1.0, codes_out=c,
                          scales_out=s[:nb].view(ROWS, COLS // b), sse_out=e[:nb].view(ROWS, COLS // b))
         elif kind == "absmax":
-            mxq.tensor_absmax(xs[k], out=amax_buf)
+            mxq.tensor_absmax(xs[k], out=amax_buf[k:k + 1])
         else:
-            mxq.dequantize(dq_codes, dq_scales, b, fmt, 1.0, out=deq[k % 2])
+            mxq.dequantize(dq[k][0], dq[k][1], b, fmt, 1.0, out=deq[k])
+
+    def step(events=None):
+        # one pass of the whole hot path over the batch: every pass type over all matrices;
+        # consecutive launches touch different matrices (> 1 GB between re-uses of any buffer)
+        for i, p in enumerate(passes):
+            if events is not None:
+                events[i][0].record()
+            for k in range(N_SETS):
+                launch(p, k)
+            if events is not None:
+                events[i][1].record()
 
     for _ in range(args.warmup):
-        for p in passes:
-            launch(p)
+        step()
     torch.cuda.synchronize()
 
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -159,21 +199,24 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        for i, p in enumerate(passes):
-            ev[s][i][0].record()
-            launch(p)
-            ev[s][i][1].record()
+        step(ev[s])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    if args.calibrate_copy:
+        for k in range(N_SETS):
+            deq[k].copy_(xs[k])                       # 117 440 512 bytes read + the same written
+        torch.cuda.synchronize()
+
     ms_per_step = dt / args.steps * 1e3
-    value = n_quant * N_ELEM / (dt / args.steps) / 1e9
+    value = n_quant * N_SETS * N_ELEM / (dt / args.steps) / 1e9
 
     kern = []
     for i, p in enumerate(passes):
         kind, name, b, fmt, rec, hier = p
-        ms = float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)]))
-        row = {"name": name, "ms": round(ms, 4), "gelem_s": round(N_ELEM / ms / 1e6, 1)}
+        # average duration of ONE launch: events bracket N_SETS back-to-back launches
+        ms = float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)])) / N_SETS
+        row = {"name": name, "ms": round(ms, 5), "gelem_s": round(N_ELEM / ms / 1e6, 1)}
         if rec == BRUTE and kind == "quant":
             flops = N_ELEM * NCAND[fmt] * 6.0
             row.update(bound="alu", tflop_s=round(flops / ms / 1e9, 2),
@@ -184,34 +227,43 @@ def main():
                        frac=round(by / ms / 1e6 / HBM_PEAK_GBS, 4))
         kern.append(row)
 
-    dom = max(kern, key=lambda r: r["ms"])
-    if dom["bound"] == "alu":
-        roofline = {"bound": "alu", "kernel": dom["name"], "achieved": dom["tflop_s"],
-                    "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"],
-                    "traffic": None, "avg_launch_ms": dom["ms"],
-                    "note": "6 flops per (element x candidate): scale, round, residual FMA, square-add FMA"}
-    else:
-        roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": dom["gb_s"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": dom["frac"], "traffic": None, "avg_launch_ms": dom["ms"]}
-    st = next(r for r in kern if r["name"] == "absmax_e4m3_b16")
-    roofline_stream = {"bound": "hbm", "kernel": st["name"], "achieved": st["gb_s"], "peak": HBM_PEAK_GBS,
-                       "unit": "GB/s", "frac": st["frac"], "traffic": None, "avg_launch_ms": st["ms"],
-                       "bytes_per_elem": 2.8125}
+    def roof(r, extra=None):
+        if r["bound"] == "alu":
+            d = {"bound": "alu", "kernel": r["name"], "achieved": r["tflop_s"],
+                 "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": r["frac"], "traffic": measured_traffic(r["name"]),
+                 "avg_launch_ms": r["ms"],
+                 "note": "algorithmic work = 6 flops per (element x candidate): scale, round, residual "
+                         "FMA, square + add; peak is the packed-FMA fp32 vector peak"}
+        else:
+            d = {"bound": "hbm", "kernel": r["name"], "achieved": r["gb_s"], "peak": HBM_PEAK_GBS,
+                 "unit": "GB/s", "frac": r["frac"], "traffic": measured_traffic(r["name"]),
+                 "avg_launch_ms": r["ms"]}
+        if extra:
+            d.update(extra)
+        return d
 
+    dom = max(kern, key=lambda r: r["ms"])
     out = {
         "metric": "GElem/s quantized per recipe (absmax, 4-over-6, brute-force); % HBM/VALU roof",
         "value": round(value, 3), "unit": "GElem/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "bf16 4096x14336 Student-t(df=4)*0.02 weights; one step = "
-                               f"{n_quant} quantise passes (12 streaming E4M3 b8-64, 2 hierarchical, "
-                               "E8M0, UE5M3, 4 brute-force) + tensor abs-max + de-quantise",
-                   "elements": N_ELEM, "quantise_passes_per_step": n_quant, "tensor_scale": T},
+        "config": {"workload": f"batch of {N_SETS} bf16 4096x14336 Student-t(df=4)*0.02 weight matrices; "
+                               f"one step = {n_quant} quantise passes per matrix (12 streaming E4M3 "
+                               "b8-64, 2 hierarchical, E8M0, UE5M3, 4 brute-force) + tensor abs-max + "
+                               "de-quantise",
+                   "elements_per_matrix": N_ELEM, "matrices": N_SETS,
+                   "quantise_passes_per_matrix": n_quant, "tensor_scale": T},
         "per_recipe_gelem_s": {r["name"]: r["gelem_s"] for r in kern},
-        "roofline": roofline,
-        "roofline_stream": roofline_stream,
+        "roofline": roof(dom),
         "kernels": kern,
     }
+    st = [r for r in kern if r["name"] == "absmax_e4m3_b16"]
+    if st:
+        out["roofline_stream"] = roof(st[0], {"bytes_per_elem": 2.8125})
+    f6 = [r for r in kern if r["name"] == "4over6_e4m3_b16"]
+    if f6:
+        out["roofline_4over6"] = roof(f6[0], {"bytes_per_elem": 2.8125})
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(x_np, passes, T, args.cpu_rows)
     print(json.dumps(out))

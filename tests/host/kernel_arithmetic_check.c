@@ -1,0 +1,209 @@
+/*
+ * CPU emulation of the arithmetic shortcuts the HIP kernels take, checked against the plain
+ * definitions over (near-)exhaustive input sets.  This file shares nothing with the oracle:
+ * it re-states, with fmaf on the host, the exact instruction sequences of
+ * paper_2605_08565_amd/csrc (make_recip / quot, the scale encode of amax/6 and amax/4, the
+ * power-of-two code of Eq. 1, the reciprocal-refined division by the per-tensor scale) and
+ * compares every DECISION they lead to with exact arithmetic in double precision.
+ *
+ * Prints one line per check: "<name> cases=<n> bad=<m>"; exit status 0 iff all bad == 0.
+ * Build: gcc -O2 -ffp-contract=off -mfma -fopenmp.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+static inline float u2f(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static inline uint32_t f2u(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+/* the kernel's reciprocal split: r_hi = 1/d rounded toward zero, r_lo = fl(rho * r_hi) */
+static void make_recip(float d, float* hi, float* lo)
+{
+    volatile float r = 1.0f / d;
+    if (fmaf(-r, d, 1.0f) < 0.0f) r = u2f(f2u(r) - 1u);
+    float rho = fmaf(-r, d, 1.0f);
+    *hi = r;
+    *lo = rho * r;
+}
+static inline float quot(float v, float hi, float lo) { volatile float p = v * lo; return fmaf(v, hi, p); }
+
+/* E2M1 magnitude index by the conversion instruction's rule (RNE, saturate) */
+static int e2m1_index(double ay)
+{
+    return (ay > 0.25) + (ay >= 0.75) + (ay > 1.25) + (ay >= 1.75) + (ay > 2.5) + (ay >= 3.5) + (ay > 5.0);
+}
+/* the same decision taken exactly: compare v with t*S (exact products in double) */
+static int e2m1_index_exact(double v, double S)
+{
+    static const double t[7] = {0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0};
+    static const int incl[7] = {0, 1, 0, 1, 0, 1, 0};
+    int m = 0;
+    for (int i = 0; i < 7; ++i) m += incl[i] ? (v >= t[i] * S) : (v > t[i] * S);
+    return m;
+}
+
+/* check 1: quotient decisions for every fp32 mantissa of v, every scale mantissa, and the
+ * binades of v/S that contain a rounding threshold */
+static long check_quot(long* cases)
+{
+    long bad = 0, n = 0;
+    for (int mi = 0; mi < 8; ++mi) {
+        const float S = 1.0f + mi * 0.125f;
+        float hi, lo;
+        make_recip(S, &hi, &lo);
+#pragma omp parallel for reduction(+ : bad, n) schedule(static)
+        for (int64_t m = 0; m < (1 << 23); ++m) {
+            for (int e = -4; e <= 3; ++e) {
+                const float v = ldexpf(u2f(0x3F800000u | (uint32_t)m), e);
+                const int a = e2m1_index((double)quot(v, hi, lo));
+                const int b = e2m1_index_exact((double)v, (double)S);
+                ++n;
+                if (a != b) ++bad;
+            }
+        }
+    }
+    *cases = n;
+    return bad;
+}
+
+/* the kernel's manual Round_SF (8-bit float, bias, clip) */
+static uint32_t sf_encode(float y, int bias, float maxv)
+{
+    if (y > maxv) y = maxv;
+    const uint32_t b = f2u(y);
+    const uint32_t nrm = ((b + 0x7FFFFu + ((b >> 20) & 1u)) >> 20) - ((127u - bias) << 3);
+    const float magic = u2f((uint32_t)(127 + (1 - bias) + 20) << 23);
+    volatile float t = y + magic;
+    const uint32_t sub = f2u(t) - f2u(magic);
+    const float min_normal = u2f((uint32_t)(127 + 1 - bias) << 23);
+    return (y < min_normal) ? sub : nrm;
+}
+static double sf_value(int bias, int c)
+{
+    const int e = c >> 3, m = c & 7;
+    return e ? ldexp(1.0 + m / 8.0, e - bias) : ldexp((double)m, 1 - bias - 3);
+}
+/* exact nearest-even code of a/M: walk up from the kernel's answer's neighbourhood */
+static int sf_exact(double a, double M, int bias, int maxc)
+{
+    /* a/M compared with midpoints mu via a ? M*mu (exact: mu has <= 5 significant bits, M <= 3) */
+    int lo = 0, hi = maxc;
+    while (lo < hi) {                       /* largest c with value(c) <= a/M */
+        const int mid = (lo + hi + 1) / 2;
+        if (M * sf_value(bias, mid) <= a) lo = mid; else hi = mid - 1;
+    }
+    if (lo == maxc) return maxc;
+    const double mu = (sf_value(bias, lo) + sf_value(bias, lo + 1)) / 2;
+    if (a > M * mu) return lo + 1;
+    if (a < M * mu) return lo;
+    return (lo % 2 == 0) ? lo : lo + 1;
+}
+
+static long check_scale_encode(long* cases)
+{
+    const float sixth_hi = (float)(1.0 / 6.0), sixth_lo = (float)(1.0 / 6.0 - (double)(float)(1.0 / 6.0));
+    long bad = 0, n = 0;
+    for (int f = 0; f < 2; ++f) {
+        const int bias = f ? 15 : 7, maxc = f ? 0xFE : 0x7E;
+        const float maxv = (float)sf_value(bias, maxc);
+        const int e_lo = 1 - bias - 3 - 3, e_hi = (maxc >> 3) - bias + 4;
+#pragma omp parallel for reduction(+ : bad, n) schedule(static)
+        for (int64_t m = 0; m < (1 << 23); m += 3) {
+            for (int e = e_lo; e <= e_hi; ++e) {
+                const float a = ldexpf(u2f(0x3F800000u | (uint32_t)m), e);
+                volatile float p = a * sixth_lo;
+                const float y6 = fmaf(a, sixth_hi, p);
+                const float y4 = a * 0.25f;
+                n += 2;
+                if ((int)sf_encode(y6, bias, maxv) != sf_exact((double)a, 6.0, bias, maxc)) ++bad;
+                if ((int)sf_encode(y4, bias, maxv) != sf_exact((double)a, 4.0, bias, maxc)) ++bad;
+            }
+        }
+    }
+    *cases = n;
+    return bad;
+}
+
+/* check 3: Eq. 1 code from the bit pattern vs floor(log2(a/6)) by exact comparison */
+static long check_pow2(long* cases)
+{
+    long bad = 0, n = 0;
+#pragma omp parallel for reduction(+ : bad, n) schedule(static)
+    for (int64_t b = 0; b < 0x7F800000LL; b += 5) {
+        const float a = u2f((uint32_t)b);
+        const int c = (int)(b >> 23) - 3 + (int)((b >> 22) & 1);
+        const int got = c < 0 ? 0 : c;
+        int want = 0;
+        if (a > 0.0f) {
+            int ex;
+            const double fr = frexp((double)a / 6.0, &ex);    /* a/6 = fr * 2^ex, fr in [.5,1): not exact */
+            (void)fr;
+            int k = ex - 1;                                   /* candidate floor(log2) */
+            while (ldexp(6.0, k) > (double)a) --k;            /* exact comparisons fix it */
+            while (ldexp(6.0, k + 1) <= (double)a) ++k;
+            want = k + 127;
+            if (want < 0) want = 0;
+            if (want > 254) want = 254;
+        }
+        ++n;
+        if (got != want) ++bad;
+    }
+    *cases = n;
+    return bad;
+}
+
+/* check 4: division by the per-tensor scale, reciprocal + two FMA refinements */
+static float div_by_T(float v, float T, float rT)
+{
+    volatile float q0 = v * rT;
+    volatile float q1 = fmaf(fmaf(-q0, T, v), rT, q0);
+    volatile float q2 = fmaf(fmaf(-q1, T, v), rT, q1);
+    return u2f((f2u(q2) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
+}
+static long check_div(long* cases)
+{
+    long bad = 0, n = 0;
+#pragma omp parallel for reduction(+ : bad, n) schedule(dynamic, 8)
+    for (int ti = 0; ti < 3000; ++ti) {
+        uint64_t rng = 88172645463325252ull + 7919ull * (uint64_t)ti;
+#define NEXT() (rng ^= rng << 13, rng ^= rng >> 7, rng ^= rng << 17, rng)
+        uint32_t tm = (uint32_t)(NEXT() & 0x7FFFFF);
+        if (ti < 32) tm = 0x7FFFFEu - (uint32_t)ti;           /* near all-ones mantissas */
+        const int te = (int)(NEXT() % 41) - 20;
+        const float T = ldexpf(u2f(0x3F800000u | tm), te);
+        if (!(T >= 0x1p-20f && T <= 0x1p20f)) continue;
+        volatile float rT = 1.0f / T;
+        for (uint32_t b = 0; b < 0x10000; ++b) {              /* every bf16 value */
+            const float v = u2f(b << 16);
+            if (isnan(v) || isinf(v)) continue;
+            const float q = v / T;
+            const float aq = fabsf(q);
+            if (aq != 0.0f && (aq < 0x1p-40f || aq > 0x1p90f)) continue;   /* handled by the fall-back */
+            ++n;
+            if (f2u(div_by_T(v, T, rT)) != f2u(q)) ++bad;
+        }
+        for (int k = 0; k < 30000; ++k) {                     /* random fp32 values */
+            const uint32_t u = (uint32_t)NEXT();
+            const int e = (int)(NEXT() % 121) - 60;
+            const float v = ldexpf(u2f(0x3F800000u | (u & 0x7FFFFF)), e) * ((u >> 31) ? -1.0f : 1.0f);
+            const float q = v / T;
+            const float aq = fabsf(q);
+            if (aq < 0x1p-40f || aq > 0x1p90f) continue;
+            ++n;
+            if (f2u(div_by_T(v, T, rT)) != f2u(q)) ++bad;
+        }
+    }
+    *cases = n;
+    return bad;
+}
+
+int main(void)
+{
+    long n, bad, total = 0;
+    bad = check_quot(&n);          printf("quotient_decisions cases=%ld bad=%ld\n", n, bad); total += bad;
+    bad = check_scale_encode(&n);  printf("scale_encode cases=%ld bad=%ld\n", n, bad); total += bad;
+    bad = check_pow2(&n);          printf("pow2_code cases=%ld bad=%ld\n", n, bad); total += bad;
+    bad = check_div(&n);           printf("tensor_scale_division cases=%ld bad=%ld\n", n, bad); total += bad;
+    return total == 0 ? 0 : 1;
+}
