@@ -1,0 +1,53 @@
+"""The paper's numerical study (Section 3.1) run through the GPU library: parity with the oracle
+on a slice of it, and the qualitative findings of the MSE-vs-sigma figure on the full grid."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def result():
+    from paper_2605_08565_amd import study
+    assert torch.cuda.is_available()
+    return study.run(n_sigmas=151, blocks_per_sigma=50000)
+
+
+def test_study_parity_slice(oracle):
+    """Seven sigmas x 2 000 blocks, every recipe and block size, bit-exact against the oracle."""
+    from paper_2605_08565_amd import mxq, study
+    sig = study.study_sigmas(151)[[0, 1, 5, 12, 30, 90, 150]]
+    for b in study.BLOCKS:
+        x = study.study_tensor(sig, 2000, b, seed=99)
+        xt = mxq.from_bits(x)
+        for name, rec in study.RECIPES.items():
+            print(f"[study-parity] b={b} recipe={name}", flush=True)
+            c, s, e = mxq.quantize(xt, b, 1, rec)
+            oc, os_, oe = oracle.quantize(x, b, 1, rec)
+            assert (c.cpu().numpy() == oc).all() and (s.cpu().numpy() == os_).all()
+            assert (e.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
+
+
+def test_study_regions(result):
+    sig = np.array(result["sigma"])
+    m = {r: {int(b): np.array(v) / sig ** 2 for b, v in d.items()} for r, d in result["mse"].items()}
+    small = sig <= 0.0012                      # Region A: abs-max scales underflow to zero
+    for b in (4, 8, 16, 32):
+        assert (m["absmax"][b][small] > 0.9).all()
+        assert (m["4over6"][b][small] > 0.85).all()              # 4-over-6 alone keeps the bump
+        assert (m["prevent_zero"][b][small] < 0.35).all()         # prevent-zero removes it
+        assert np.allclose(m["brute_force"][b][small], m["prevent_zero"][b][small], rtol=2e-2)
+    mid = (sig >= 0.007) & (sig <= 0.009)      # Region B: inversion under prevent-zero ...
+    assert (m["prevent_zero"][4][mid] > m["prevent_zero"][32][mid]).all()
+    assert (m["prevent_zero_4over6"][4][mid] < m["prevent_zero_4over6"][32][mid]).all()   # ... resolved
+    big = sig >= 0.03                          # Region C
+    assert (m["absmax"][4][big] < m["absmax"][32][big]).all()
+    assert (m["4over6"][4][big] < 0.75 * m["absmax"][4][big]).all()
+    # brute force: lowest everywhere, and monotone in block size up to sampling noise
+    # (each block size draws its own 50 000 blocks, as in the paper)
+    for r in ("absmax", "prevent_zero", "4over6", "prevent_zero_4over6"):
+        for b in (4, 8, 16, 32):
+            assert (m["brute_force"][b] <= m[r][b] * (1 + 1e-9)).all()
+    for lo, hi in ((4, 8), (8, 16), (16, 32)):
+        assert (m["brute_force"][lo] <= m["brute_force"][hi] * 1.02).all()
