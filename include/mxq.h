@@ -122,6 +122,33 @@ MXQ_API int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
 MXQ_API int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
                       float* absmax_out, void* stream);
 
+/*
+ * mxq_clip_sse -- diagnostic of the paper's appendix ("Clipping only MSE"): for every block,
+ * the part of the squared error that comes from elements saturating at the largest E2M1
+ * magnitude: sum over the elements with |v_i / S| > 6 of (v_i - sign(v_i) * 6 * S)^2, with
+ * v_i = x_i / tensor_scale and S the block's scale byte; elements that do not clip contribute
+ * +0; same fp32 tree as the block SSE.  Works on the scales written by any recipe.
+ *
+ *   x               device, as for mxq_quantize
+ *   scales          device, rows*cols/block bytes, 4-byte aligned
+ *   clip_sse_out    device, rows*cols/block floats, 16-byte aligned
+ */
+MXQ_API int mxq_clip_sse(const void* x, const uint8_t* scales, int64_t rows, int64_t cols, int block,
+                         int elem_fmt, int scale_fmt, float tensor_scale, float* clip_sse_out,
+                         int x_dtype, void* stream);
+
+/*
+ * mxq_histogram -- diagnostic of the paper's appendix (entry and scale histograms): counts of
+ * the 8 E2M1 magnitude indices over all elements and of the 256 scale bytes over all blocks.
+ *
+ *   codes, scales   device, layouts as written by mxq_quantize, 4-byte aligned
+ *   elem_hist       device, 8 x uint64, 8-byte aligned, overwritten
+ *   scale_hist      device, 256 x uint64, 8-byte aligned, overwritten
+ */
+MXQ_API int mxq_histogram(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                          int block, int elem_fmt, uint64_t* elem_hist, uint64_t* scale_hist,
+                          void* stream);
+
 /* Host helper: the per-tensor scale that maps the tensor abs-max onto (largest element
  * value) x (largest scale value): absmax / (6 * SF_max), e.g. absmax / 2688 for E4M3; 1 for
  * an all-zero tensor or a format whose range makes the quotient vanish.  NaN on a bad enum. */

@@ -64,6 +64,8 @@ def _load():
     lib.orc_quantize.argtypes = [vp, i32, i64, i64, i32, i32, i32, f32, i32, vp, vp, vp, vp]
     lib.orc_block_sse.restype = i32
     lib.orc_block_sse.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    lib.orc_clip_sse.restype = i32
+    lib.orc_clip_sse.argtypes = [vp, i32, i64, i64, i32, i32, f32, vp, vp]
     lib.orc_dequantize.restype = i32
     lib.orc_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, f32, vp, i32]
     lib.orc_tensor_absmax.restype = f32
@@ -165,6 +167,29 @@ def dequantize(codes: np.ndarray, scales: np.ndarray, block: int, scale_fmt: int
     if rc != 0:
         raise ValueError("orc_dequantize rejected its arguments")
     return out
+
+
+def clip_sse(x: np.ndarray, scales: np.ndarray, block: int, scale_fmt: int,
+             tensor_scale: float = 1.0) -> np.ndarray:
+    """Clipping-only block SSE for the given scale bytes (f32 [R, C/block])."""
+    x = np.ascontiguousarray(x)
+    scales = np.ascontiguousarray(scales, np.uint8)
+    rows, cols = x.shape
+    out = np.empty((rows, cols // block), np.float32)
+    rc = _load().orc_clip_sse(_ptr(x), _dtype_of(x), rows, cols, block, scale_fmt,
+                              float(np.float32(tensor_scale)), _ptr(scales), _ptr(out))
+    if rc != 0:
+        raise ValueError("orc_clip_sse rejected its arguments")
+    return out
+
+
+def histograms(codes: np.ndarray, scales: np.ndarray):
+    """Appendix histograms: counts of the 8 E2M1 magnitude indices over all elements and of the
+    256 scale bytes over all blocks (uint64 [8], uint64 [256])."""
+    codes = np.ascontiguousarray(codes, np.uint8).ravel()
+    mags = np.concatenate([codes & 7, (codes >> 4) & 7])
+    return (np.bincount(mags, minlength=8).astype(np.uint64),
+            np.bincount(np.ascontiguousarray(scales, np.uint8).ravel(), minlength=256).astype(np.uint64))
 
 
 def tensor_absmax(x: np.ndarray) -> float:

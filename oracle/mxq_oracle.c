@@ -372,6 +372,40 @@ int orc_block_sse(const float* v, int block, int scale_fmt, int code,
     return 0;
 }
 
+/* Clipping-only part of the block SSE (appendix figure "Clipping only MSE"): the squared
+ * error of the elements whose quotient v_i / S lies beyond the largest E2M1 magnitude 6, i.e.
+ * that saturate; every other element contributes +0.  Same fp32 tree as the block SSE.  The
+ * paper shows this quantity only as a figure; taking "the clipping portion" of the MSE to be
+ * the error of the saturating elements is this build's reading.  scales holds one byte per
+ * block, as written by orc_quantize. */
+int orc_clip_sse(const void* x, int x_dtype, int64_t rows, int64_t cols, int block, int scale_fmt,
+                 float tensor_scale, const uint8_t* scales, float* clip_sse)
+{
+    if (!x || !scales || !clip_sse) return -1;
+    if (rows < 0 || cols < 0 || !valid_block(block) || cols % block != 0) return -1;
+    int64_t nb = rows * cols / block;
+#pragma omp parallel for schedule(static)
+    for (int64_t blk = 0; blk < nb; ++blk) {
+        float sq[128];
+        float S = orc_scale_decode(scale_fmt, scales[blk]);
+        for (int i = 0; i < block; ++i) {
+            float v = load_elem(x, x_dtype, blk * block + i);
+            if (tensor_scale != 1.0f) v = v / tensor_scale;
+            sq[i] = 0.0f;
+            if (S > 0.0f) {
+                float y = v / S;
+                if (fabsf(y) > E2M1_SET[7]) {
+                    float q = signbit(v) ? -E2M1_SET[7] : E2M1_SET[7];
+                    float e = v - q * S;
+                    sq[i] = e * e;
+                }
+            }
+        }
+        clip_sse[blk] = tree_sum(sq, 0, block);
+    }
+    return 0;
+}
+
 static uint16_t f32_to_bf16_rne(float f)
 {
     uint32_t u;

@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmxq.so")
-SOURCES = ["mxq_api.hip", "stream_kernels.hip", "brute_kernels.hip", "aux_kernels.hip"]
+SOURCES = ["mxq_api.hip", "stream_kernels.hip", "brute_kernels.hip", "aux_kernels.hip", "diag_kernels.hip"]
 
 # No fast-math and no FMA contraction: every rounding in the kernels is written out.
 # Packed-fp32 instructions are switched off for the device compiler.

@@ -98,6 +98,43 @@ int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
                ? MXQ_OK : MXQ_ERR_HIP;
 }
 
+int mxq_clip_sse(const void* x, const uint8_t* scales, int64_t rows, int64_t cols, int block,
+                 int elem_fmt, int scale_fmt, float tensor_scale, float* clip_sse_out,
+                 int x_dtype, void* stream)
+{
+    if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
+    if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
+    if (elem_fmt != MXQ_ELEM_E2M1) return MXQ_ERR_INVALID_ARG;
+    if (scale_fmt < MXQ_SCALE_E8M0 || scale_fmt > MXQ_SCALE_UE5M3) return MXQ_ERR_INVALID_ARG;
+    if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
+    if (!(tensor_scale > 0.0f) || std::isinf(tensor_scale)) return MXQ_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
+    const int64_t n = rows * cols;
+    if (n == 0) return MXQ_OK;
+    if (!x || !scales || !clip_sse_out) return MXQ_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(scales, 4) || !aligned(clip_sse_out, 16)) return MXQ_ERR_ALIGNMENT;
+    return mxq::launch_clip_sse(x, scales, n, x_dtype, block, scale_fmt, tensor_scale, clip_sse_out,
+                                static_cast<hipStream_t>(stream)) == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+int mxq_histogram(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
+                  int block, int elem_fmt, uint64_t* elem_hist, uint64_t* scale_hist, void* stream)
+{
+    if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
+    if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
+    if (elem_fmt != MXQ_ELEM_E2M1) return MXQ_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
+    if (!elem_hist || !scale_hist) return MXQ_ERR_INVALID_ARG;
+    const int64_t n = rows * cols;
+    if (n > 0 && (!codes || !scales)) return MXQ_ERR_INVALID_ARG;
+    if (!aligned(elem_hist, 8) || !aligned(scale_hist, 8)) return MXQ_ERR_ALIGNMENT;
+    if (n > 0 && (!aligned(codes, 4) || !aligned(scales, 4))) return MXQ_ERR_ALIGNMENT;
+    return mxq::launch_histogram(codes, scales, n, block,
+                                 reinterpret_cast<unsigned long long*>(elem_hist),
+                                 reinterpret_cast<unsigned long long*>(scale_hist),
+                                 static_cast<hipStream_t>(stream)) == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
 float mxq_tensor_scale_from_absmax(float absmax, int elem_fmt, int scale_fmt)
 {
     if (elem_fmt != MXQ_ELEM_E2M1) return NAN;

@@ -43,6 +43,11 @@ inline int stream_grid(int64_t n_chunks)
 hipError_t launch_stream(const StreamArgs& a);       // ABSMAX, ABSMAX_PZ, 4OVER6, 4OVER6_PZ
 hipError_t launch_brute(const StreamArgs& a);        // BRUTE
 hipError_t launch_dequant(const DequantArgs& a);
+hipError_t launch_clip_sse(const void* x, const uint8_t* scales, int64_t n, int dtype, int block,
+                           int scale_fmt, float T, float* out, hipStream_t stream);
+hipError_t launch_histogram(const uint8_t* codes, const uint8_t* scales, int64_t n, int block,
+                            unsigned long long* elem_hist, unsigned long long* scale_hist,
+                            hipStream_t stream);
 hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, hipStream_t stream);
 
 }  // namespace mxq

@@ -45,6 +45,10 @@ def lib() -> ctypes.CDLL:
     L.mxq_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
     L.mxq_tensor_absmax.restype = i32
     L.mxq_tensor_absmax.argtypes = [vp, i64, i64, i32, vp, vp]
+    L.mxq_clip_sse.restype = i32
+    L.mxq_clip_sse.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
+    L.mxq_histogram.restype = i32
+    L.mxq_histogram.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp]
     L.mxq_tensor_scale_from_absmax.restype = f32
     L.mxq_tensor_scale_from_absmax.argtypes = [f32, i32, i32]
     L.mxq_scale_decode.restype = f32
@@ -125,6 +129,29 @@ def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None)
     _check(lib().mxq_tensor_absmax(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
                                    _stream_ptr(stream)))
     return out
+
+
+def clip_sse(x: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt: int,
+             tensor_scale: float = 1.0, out: torch.Tensor | None = None, stream=None,
+             elem_fmt: int = ELEM_E2M1) -> torch.Tensor:
+    """mxq_clip_sse: clipping-only part of the block SSE for the given scale bytes."""
+    rows, cols = x.shape
+    if out is None:
+        out = torch.empty((rows, cols // block), dtype=torch.float32, device=x.device)
+    _check(lib().mxq_clip_sse(x.data_ptr(), scales.data_ptr(), rows, cols, block, elem_fmt, scale_fmt,
+                              float(tensor_scale), out.data_ptr(), _dtype_code(x), _stream_ptr(stream)))
+    return out
+
+
+def histogram(codes: torch.Tensor, scales: torch.Tensor, block: int, stream=None,
+              elem_fmt: int = ELEM_E2M1):
+    """mxq_histogram: (int64 [8] magnitude-index counts, int64 [256] scale-byte counts)."""
+    rows, half = codes.shape
+    eh = torch.empty(8, dtype=torch.int64, device=codes.device)
+    sh = torch.empty(256, dtype=torch.int64, device=codes.device)
+    _check(lib().mxq_histogram(codes.data_ptr(), scales.data_ptr(), rows, half * 2, block, elem_fmt,
+                               eh.data_ptr(), sh.data_ptr(), _stream_ptr(stream)))
+    return eh, sh
 
 
 def tensor_scale_from_absmax(absmax: float, scale_fmt: int, elem_fmt: int = ELEM_E2M1) -> float:

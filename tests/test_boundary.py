@@ -28,7 +28,8 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_dequantize", "mxq_tensor_absmax",
+    assert names == sorted(["mxq_quantize", "mxq_dequantize", "mxq_tensor_absmax", "mxq_clip_sse",
+                            "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
                             "mxq_num_candidates", "mxq_status_string"])
     L = ctypes.CDLL(mxq.LIB_PATH)
@@ -96,6 +97,21 @@ def test_argument_validation_without_a_launch(mxq):
     assert d(T=0.0) == mxq.ERR_INVALID_ARG
     assert d(out=P + 8) == mxq.ERR_ALIGNMENT
     assert d(rows=0) == mxq.OK
+
+    def cl(x=P, scales=P, rows=4, cols=64, block=16, elem=0, fmt=1, T=1.0, out=P, dt=0):
+        return L.mxq_clip_sse(x, scales, rows, cols, block, elem, fmt, T, out, dt, None)
+
+    assert cl(x=None) == mxq.ERR_INVALID_ARG and cl(scales=None) == mxq.ERR_INVALID_ARG
+    assert cl(out=None) == mxq.ERR_INVALID_ARG and cl(block=7) == mxq.ERR_INVALID_ARG
+    assert cl(T=-2.0) == mxq.ERR_INVALID_ARG and cl(fmt=4) == mxq.ERR_INVALID_ARG
+    assert cl(out=P + 4) == mxq.ERR_ALIGNMENT and cl(rows=0) == mxq.OK
+
+    def hi(codes=P, scales=P, rows=4, cols=64, block=16, elem=0, eh=P, sh=P):
+        return L.mxq_histogram(codes, scales, rows, cols, block, elem, eh, sh, None)
+
+    assert hi(codes=None) == mxq.ERR_INVALID_ARG and hi(eh=None) == mxq.ERR_INVALID_ARG
+    assert hi(sh=None) == mxq.ERR_INVALID_ARG and hi(cols=70) == mxq.ERR_INVALID_ARG
+    assert hi(eh=P + 4) == mxq.ERR_ALIGNMENT and hi(codes=P + 2) == mxq.ERR_ALIGNMENT
 
     assert L.mxq_tensor_absmax(P, 4, 4, 0, None, None) == mxq.ERR_INVALID_ARG
     assert L.mxq_tensor_absmax(None, 4, 4, 0, P, None) == mxq.ERR_INVALID_ARG

@@ -306,3 +306,46 @@ def test_config5_layer0_sampled(oracle, mxq):
                 torch.cuda.synchronize()
                 r = rows[:2] if rec == 4 else rows
                 check_rows(oracle, x_np, r, out, block, fmt, rec)
+
+
+# ------------------------------------------------------------------ appendix diagnostics
+
+def test_clip_sse_and_histograms(oracle, mxq):
+    """Clipping-only SSE (bit-exact) and the entry / scale histograms (exact counts) on the
+    outputs of every recipe, incl. ragged shapes, a per-tensor scale and fp32 input."""
+    cases = [(W.student_t_weights(37, 1152, seed=400), 1.0),
+             (W.normal_f32(19, 640, seed=401, sigma=0.004), 1.0),
+             (W.outlier_activations(16, 1024, seed=402), None),
+             (W.f32_to_bf16_bits(W.normal_f32(5, 12, seed=403, sigma=0.05)), 1.0),
+             (W.normal_f32(3, 6, seed=404, sigma=0.05), 0.37)]
+    for x_np, T in cases:
+        x = mxq.from_bits(x_np)
+        if T is None:
+            T = mxq.tensor_scale_from_absmax(float(mxq.tensor_absmax(x).cpu()[0]), 1)
+        for block in (2, 4, 8, 16, 32, 64, 128):
+            if x_np.shape[1] % block:
+                continue
+            for fmt, rec in [(0, 0), (1, 0), (1, 1), (1, 2), (1, 4), (2, 3)]:
+                print(f"[diag] shape={x_np.shape} b={block} fmt={fmt} rec={rec} T={T}", flush=True)
+                c, s, _ = mxq.quantize(x, block, fmt, rec, tensor_scale=T)
+                clip = mxq.clip_sse(x, s, block, fmt, tensor_scale=T).cpu().numpy()
+                eh, sh = mxq.histogram(c, s, block)
+                oc, os_, _ = oracle.quantize(x_np, block, fmt, rec, tensor_scale=T)
+                want = oracle.clip_sse(x_np, os_, block, fmt, tensor_scale=T)
+                assert (clip.view(np.uint32) == want.view(np.uint32)).all()
+                weh, wsh = oracle.histograms(oc, os_)
+                assert (eh.cpu().numpy().astype(np.uint64) == weh).all()
+                assert (sh.cpu().numpy().astype(np.uint64) == wsh).all()
+
+
+def test_histogram_full_size(oracle, mxq):
+    x_np = W.config2()
+    x = mxq.from_bits(x_np)
+    for block, rec in [(16, 0), (4, 2)]:
+        c, s, _ = mxq.quantize(x, block, 1, rec)
+        eh, sh = mxq.histogram(c, s, block)
+        torch.cuda.synchronize()
+        weh, wsh = oracle.histograms(c.cpu().numpy(), s.cpu().numpy())
+        assert (eh.cpu().numpy().astype(np.uint64) == weh).all()
+        assert (sh.cpu().numpy().astype(np.uint64) == wsh).all()
+        assert int(eh.sum()) == x_np.size and int(sh.sum()) == x_np.size // block
