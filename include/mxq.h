@@ -62,13 +62,18 @@ typedef enum { MXQ_SCALE_E8M0 = 0, MXQ_SCALE_E4M3 = 1, MXQ_SCALE_UE5M3 = 2 } mxq
  *   4OVER6_PZ  both candidates clamped by Eq. 3 first (Fig. 1(d) of the paper).
  *   BRUTE      every finite, strictly positive scale code is tried; the lowest code of
  *              minimal SSE is kept (brute-force paragraph, Section 2).
- * 4OVER6*, BRUTE with E8M0 return MXQ_ERR_UNSUPPORTED. */
+ *   BRUTE_PRUNED  the same result as BRUTE, bit for bit, but candidates that provably cannot
+ *              win are skipped (scales so large that the block quantises to zero, scales so
+ *              small that the clipping error of the abs-max element alone exceeds the SSE of
+ *              the abs-max scale).  A step toward cheaper near-optimal selection (Conclusion).
+ * 4OVER6*, BRUTE* with E8M0 return MXQ_ERR_UNSUPPORTED. */
 typedef enum {
     MXQ_RECIPE_ABSMAX = 0,
     MXQ_RECIPE_ABSMAX_PZ = 1,
     MXQ_RECIPE_4OVER6 = 2,
     MXQ_RECIPE_4OVER6_PZ = 3,
-    MXQ_RECIPE_BRUTE = 4
+    MXQ_RECIPE_BRUTE = 4,
+    MXQ_RECIPE_BRUTE_PRUNED = 5
 } mxq_recipe;
 
 typedef enum { MXQ_DT_BF16 = 0, MXQ_DT_F32 = 1 } mxq_dtype;

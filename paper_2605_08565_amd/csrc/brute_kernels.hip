@@ -77,14 +77,94 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
     }
 }
 
-// Full search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE.
+// ---------------------------------------------------------------------------------------
+// Pruned search (recipe BRUTE_PRUNED): same result as the full enumeration, bit for bit,
+// fewer candidates.  Two facts bound the useful codes of a block with abs-max `amax`:
+//   (hi) S >= 4*amax quantises every element to zero, so all such candidates share one SSE
+//        (sum of squares); the first of them has the lowest code, the others can only tie.
+//   (lo) while 6*S < amax the abs-max element saturates and alone contributes
+//        fl(fl(amax - 6S)^2); fp32 sums of non-negative terms never fall below a term, so that
+//        is a lower bound of the candidate's SSE.  Once it exceeds U, the SSE of a reference
+//        candidate (the abs-max scale), the candidate cannot win; the bound falls with S, so
+//        the losers form a prefix of the code range, found by bisection.
+// The scan stays wave-uniform: the wavefront visits the union of its blocks' windows, widened
+// to whole binades.
+// ---------------------------------------------------------------------------------------
+template <int FMT>
+__device__ __forceinline__ uint32_t ceil_code(float y)      // smallest code >= 1 with value >= y
+{
+    uint32_t c = sf_encode_rne<FMT>(y);
+    if (sf_decode<FMT>(c) < y) c = min(c + 1u, (uint32_t)ScaleFmt<FMT>::kMaxCode);
+    return max(c, 1u);
+}
+
 template <int B, int FMT>
+__device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t& lo_w, uint32_t& hi_w)
+{
+    constexpr int NBLK = BruteState<B>::NBLK;
+    constexpr int LANES = (B < 8) ? 1 : B / 8;
+    constexpr int EPB = (B < 8) ? B : 8;
+    float amax[NBLK], y[8], S[NBLK];
+    uint32_t cref[NBLK];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) a = fmaxf(a, __builtin_fabsf(v[k * EPB + i]));
+        amax[k] = group_max<LANES>(a);
+        cref[k] = max(sf_encode_rne<FMT>(__builtin_fmaf(amax[k], kSixthHi, amax[k] * kSixthLo)), 1u);
+        S[k] = sf_decode<FMT>(cref[k]);
+        const Recip r = make_recip(S[k]);
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
+    }
+    const uint32_t packed = e2m1_pack8(y, 1.0f);
+    float q[8], sq[8], U[4];
+    e2m1_unpack8(packed, 1.0f, q);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { const float e = __builtin_fmaf(-q[j], S[j / EPB], v[j]); sq[j] = e * e; }
+    const float p0 = sq[0] + sq[1], p1 = sq[2] + sq[3], p2 = sq[4] + sq[5], p3 = sq[6] + sq[7];
+    if constexpr (B == 2) { U[0] = p0; U[1] = p1; U[2] = p2; U[3] = p3; }
+    else if constexpr (B == 4) { U[0] = p0 + p1; U[1] = p2 + p3; }
+    else U[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
+
+    uint32_t lo_all = 0xFFFFFFFFu, hi_all = 0u;
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        uint32_t lo = 1u, hi = cref[k];                 // the bound at cref is <= U: not a loser
+#pragma unroll 1
+        for (int it = 0; it < 8; ++it) {
+            if (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                const float lim = 6.0f * sf_decode<FMT>(mid);
+                const float d = amax[k] - lim;
+                const bool loser = (lim < amax[k]) && (d * d > U[k]);
+                if (loser) lo = mid + 1u; else hi = mid;
+            }
+        }
+        lo_all = min(lo_all, lo);
+        hi_all = max(hi_all, ceil_code<FMT>(4.0f * amax[k]));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        lo_all = min(lo_all, (uint32_t)__shfl_xor((int)lo_all, off, 64));
+        hi_all = max(hi_all, (uint32_t)__shfl_xor((int)hi_all, off, 64));
+    }
+    lo_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_all);
+    hi_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_all);
+}
+
+// Search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE.
+template <int B, int FMT, bool PRUNE>
 __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int EPB = (B < 8) ? B : 8;
     constexpr int bias = ScaleFmt<FMT>::kBias;
     constexpr int emin = 1 - bias;                                      // exponent of the first binade
+
+    uint32_t lo_w = 1u, hi_w = (uint32_t)ScaleFmt<FMT>::kMaxCode;
+    if constexpr (PRUNE) prune_window<B, FMT>(v, lo_w, hi_w);
 
     float w[8][8];
 #pragma unroll
@@ -101,16 +181,18 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
     const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
     const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
     const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
-    try_candidate<B, 0>(v, w[0], s1, 1u, st);
-    try_candidate<B, 0>(v, w[0], s2, 2u, st);
-    try_candidate<B, 4>(v, w[4], s2, 3u, st);
-    try_candidate<B, 0>(v, w[0], s4, 4u, st);
-    try_candidate<B, 2>(v, w[2], s4, 5u, st);
-    try_candidate<B, 4>(v, w[4], s4, 6u, st);
-    try_candidate<B, 6>(v, w[6], s4, 7u, st);
+    if (lo_w < 8u) {                                                    // uniform
+        try_candidate<B, 0>(v, w[0], s1, 1u, st);
+        try_candidate<B, 0>(v, w[0], s2, 2u, st);
+        try_candidate<B, 4>(v, w[4], s2, 3u, st);
+        try_candidate<B, 0>(v, w[0], s4, 4u, st);
+        try_candidate<B, 2>(v, w[2], s4, 5u, st);
+        try_candidate<B, 4>(v, w[4], s4, 6u, st);
+        try_candidate<B, 6>(v, w[6], s4, 7u, st);
+    }
 
     // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
-    for (uint32_t ef = 1u; ef <= ((uint32_t)ScaleFmt<FMT>::kMaxCode >> 3); ++ef) {
+    for (uint32_t ef = max(lo_w >> 3, 1u); ef <= (hi_w >> 3); ++ef) {
         const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
         try_binade<B, FMT, 0>(v, w, scale2, ef << 3, st);
     }
@@ -126,7 +208,7 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
     packed = e2m1_pack8(y, 1.0f);
 }
 
-template <int DT, int B, int FMT, bool HAS_T>
+template <int DT, int B, int FMT, bool HAS_T, bool PRUNE>
 __global__ void __launch_bounds__(kThreads)
 brute_kernel(const void* __restrict__ x, int64_t n_full, float T,
              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
@@ -151,7 +233,7 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T,
         }
         uint32_t packed;
         BruteState<B> st;
-        brute_search<B, FMT>(v, packed, st);
+        brute_search<B, FMT, PRUNE>(v, packed, st);
 
         if (chunk < n_full) {
             codes[chunk] = packed;
@@ -174,7 +256,7 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T,
 }
 
 // Ragged tail (n not a multiple of 8; b = 2 or 4 only): lane 0 of one wavefront.
-template <int DT, int B, int FMT, bool HAS_T>
+template <int DT, int B, int FMT, bool HAS_T, bool PRUNE>
 __global__ void __launch_bounds__(64)
 brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T,
                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
@@ -188,7 +270,7 @@ brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T,
     }
     uint32_t packed;
     BruteState<B> st;
-    brute_search<B, FMT>(v, packed, st);
+    brute_search<B, FMT, PRUNE>(v, packed, st);
     if (threadIdx.x != 0) return;
     for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
     for (int k = 0; k < NBLK; ++k) {
@@ -199,7 +281,7 @@ brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T,
     }
 }
 
-template <int DT, int B, int FMT>
+template <int DT, int B, int FMT, bool PRUNE>
 static hipError_t launch_f(const StreamArgs& a)
 {
     const int64_t n_full = a.n / 8;
@@ -209,10 +291,10 @@ static hipError_t launch_f(const StreamArgs& a)
         const int64_t need = (n_full + kThreads - 1) / kThreads;
         const dim3 grid((unsigned)(need < 256 * 8 ? need : 256 * 8)), block(kThreads);
         if (has_t)
-            hipLaunchKernelGGL((brute_kernel<DT, B, FMT, true>), grid, block, 0, a.stream,
+            hipLaunchKernelGGL((brute_kernel<DT, B, FMT, true, PRUNE>), grid, block, 0, a.stream,
                                a.x, n_full, a.T, (uint32_t*)a.codes, a.scales, a.sse);
         else
-            hipLaunchKernelGGL((brute_kernel<DT, B, FMT, false>), grid, block, 0, a.stream,
+            hipLaunchKernelGGL((brute_kernel<DT, B, FMT, false, PRUNE>), grid, block, 0, a.stream,
                                a.x, n_full, a.T, (uint32_t*)a.codes, a.scales, a.sse);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -220,10 +302,10 @@ static hipError_t launch_f(const StreamArgs& a)
     if constexpr (B < 8) {
         if (count > 0) {
             if (has_t)
-                hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, true>), dim3(1), dim3(64), 0, a.stream,
+                hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, true, PRUNE>), dim3(1), dim3(64), 0, a.stream,
                                    a.x, n_full * 8, count, a.T, a.codes, a.scales, a.sse);
             else
-                hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, false>), dim3(1), dim3(64), 0, a.stream,
+                hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, false, PRUNE>), dim3(1), dim3(64), 0, a.stream,
                                    a.x, n_full * 8, count, a.T, a.codes, a.scales, a.sse);
         }
     }
@@ -233,7 +315,9 @@ static hipError_t launch_f(const StreamArgs& a)
 template <int DT, int B>
 static hipError_t launch_b(const StreamArgs& a)
 {
-    return (a.scale_fmt == kE4M3) ? launch_f<DT, B, kE4M3>(a) : launch_f<DT, B, kUE5M3>(a);
+    const bool prune = (a.recipe == 5);
+    if (a.scale_fmt == kE4M3) return prune ? launch_f<DT, B, kE4M3, true>(a) : launch_f<DT, B, kE4M3, false>(a);
+    return prune ? launch_f<DT, B, kUE5M3, true>(a) : launch_f<DT, B, kUE5M3, false>(a);
 }
 
 template <int DT>

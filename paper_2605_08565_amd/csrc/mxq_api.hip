@@ -42,7 +42,7 @@ int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
     if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
     if (elem_fmt != MXQ_ELEM_E2M1) return MXQ_ERR_INVALID_ARG;
     if (scale_fmt < MXQ_SCALE_E8M0 || scale_fmt > MXQ_SCALE_UE5M3) return MXQ_ERR_INVALID_ARG;
-    if (recipe < MXQ_RECIPE_ABSMAX || recipe > MXQ_RECIPE_BRUTE) return MXQ_ERR_INVALID_ARG;
+    if (recipe < MXQ_RECIPE_ABSMAX || recipe > MXQ_RECIPE_BRUTE_PRUNED) return MXQ_ERR_INVALID_ARG;
     if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
     if (!(tensor_scale > 0.0f) || std::isinf(tensor_scale)) return MXQ_ERR_INVALID_ARG;
     if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
@@ -58,7 +58,7 @@ int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
     a.x = x; a.n = n; a.dtype = x_dtype; a.block = block; a.scale_fmt = scale_fmt;
     a.recipe = recipe; a.T = tensor_scale; a.codes = codes_out; a.scales = scales_out;
     a.sse = sse_out; a.stream = static_cast<hipStream_t>(stream);
-    const hipError_t e = (recipe == MXQ_RECIPE_BRUTE) ? mxq::launch_brute(a) : mxq::launch_stream(a);
+    const hipError_t e = (recipe >= MXQ_RECIPE_BRUTE) ? mxq::launch_brute(a) : mxq::launch_stream(a);
     return e == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
 }
 

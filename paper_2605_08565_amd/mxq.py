@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmxq.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_HIP = 0, -1, -2, -3, -4
 ELEM_E2M1 = 0
 SCALE_E8M0, SCALE_E4M3, SCALE_UE5M3 = 0, 1, 2
-RECIPE_ABSMAX, RECIPE_ABSMAX_PZ, RECIPE_4OVER6, RECIPE_4OVER6_PZ, RECIPE_BRUTE = 0, 1, 2, 3, 4
+RECIPE_ABSMAX, RECIPE_ABSMAX_PZ, RECIPE_4OVER6, RECIPE_4OVER6_PZ, RECIPE_BRUTE, RECIPE_BRUTE_PRUNED = 0, 1, 2, 3, 4, 5
 DT_BF16, DT_F32 = 0, 1
 
 _lib = None

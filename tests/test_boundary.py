@@ -70,12 +70,13 @@ def test_argument_validation_without_a_launch(mxq):
     assert q(cols=72, block=16) == mxq.ERR_INVALID_ARG
     assert q(elem=1) == mxq.ERR_INVALID_ARG
     assert q(fmt=3) == mxq.ERR_INVALID_ARG
-    assert q(rec=5) == mxq.ERR_INVALID_ARG
+    assert q(rec=6) == mxq.ERR_INVALID_ARG and q(rec=-1) == mxq.ERR_INVALID_ARG
     assert q(dt=2) == mxq.ERR_INVALID_ARG
     for T in (0.0, -1.0, float("inf"), float("nan")):
         assert q(T=T) == mxq.ERR_INVALID_ARG
     assert q(fmt=0, rec=2) == mxq.ERR_UNSUPPORTED
     assert q(fmt=0, rec=4) == mxq.ERR_UNSUPPORTED
+    assert q(fmt=0, rec=5) == mxq.ERR_UNSUPPORTED
     assert q(x=P + 2) == mxq.ERR_ALIGNMENT
     assert q(codes=P + 1) == mxq.ERR_ALIGNMENT
     assert q(scales=P + 2) == mxq.ERR_ALIGNMENT

@@ -12,7 +12,8 @@ from paper_2605_08565_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 FMT_NAMES = {0: "e8m0", 1: "e4m3", 2: "ue5m3"}
-REC_NAMES = {0: "absmax", 1: "absmax_pz", 2: "4over6", 3: "4over6_pz", 4: "brute"}
+REC_NAMES = {0: "absmax", 1: "absmax_pz", 2: "4over6", 3: "4over6_pz", 4: "brute", 5: "brute_pruned"}
+ORACLE_REC = {0: 0, 1: 1, 2: 2, 3: 3, 4: 4, 5: 4}      # the pruned search must equal the full one
 BLOCKS = (2, 4, 8, 16, 32, 64, 128)
 
 
@@ -27,7 +28,7 @@ def mxq():
 def combos(brute=True):
     out = [(0, 0)]
     for fmt in (1, 2):
-        for rec in (0, 1, 2, 3) + ((4,) if brute else ()):
+        for rec in (0, 1, 2, 3) + ((4, 5) if brute else ()):
             out.append((fmt, rec))
     return out
 
@@ -43,7 +44,7 @@ def check(oracle, mxq, x_np, block, fmt, rec, T=1.0, tag=""):
     print(f"[parity] {tag} shape={x_np.shape} dtype={x_np.dtype} b={block} fmt={FMT_NAMES[fmt]} "
           f"recipe={REC_NAMES[rec]} T={T}", flush=True)
     gc, gs, ge = run_gpu(mxq, x_np, block, fmt, rec, T)
-    oc, os_, oe = oracle.quantize(x_np, block, fmt, rec, tensor_scale=T)
+    oc, os_, oe = oracle.quantize(x_np, block, fmt, ORACLE_REC[rec], tensor_scale=T)
     assert (gs == os_).all(), f"scale bytes differ in {(gs != os_).sum()} blocks"
     assert (gc == oc).all(), f"code bytes differ in {(gc != oc).sum()} bytes"
     assert (ge.view(np.uint32) == oe.view(np.uint32)).all(), "block SSE not bit-identical"
@@ -82,7 +83,7 @@ def test_hierarchical_small(oracle, mxq, block):
     for fmt in (1, 2):
         T = mxq.tensor_scale_from_absmax(A, fmt)
         assert T == oracle.tensor_scale(A, fmt)
-        for rec in (0, 1, 2, 3, 4):
+        for rec in (0, 1, 2, 3, 4, 5):
             check(oracle, mxq, x, block, fmt, rec, T=T, tag="hierarchical")
     check(oracle, mxq, W.bf16_bits_to_f32(x), block, 1, 2, T=mxq.tensor_scale_from_absmax(A, 1),
           tag="hierarchical-f32")
@@ -102,7 +103,7 @@ def test_hierarchical_division_paths(oracle, mxq):
     x[9, 1::2] = -0.0
     all_ones = float(np.float32(1.99999988) * np.float32(0.0625))     # mantissa 0x7FFFFF
     for T in (0.0917, 3.0e-7, 2.0 ** 21, 2.0 ** -20, 2.0 ** 20, all_ones, 1.0000001, 7.5e-4):
-        for block, fmt, rec in [(16, 1, 0), (4, 1, 2), (64, 2, 3), (32, 0, 0), (8, 1, 4), (2, 2, 1)]:
+        for block, fmt, rec in [(16, 1, 0), (4, 1, 2), (64, 2, 3), (32, 0, 0), (8, 1, 4), (2, 2, 1), (16, 2, 5)]:
             check(oracle, mxq, x, block, fmt, rec, T=T, tag="division-paths")
     xb = W.f32_to_bf16_bits(x)
     for T in (0.0917, 3.0e-7):
@@ -234,7 +235,7 @@ def check_rows(oracle, x_np, rows, gpu_out, block, fmt, rec, T=1.0):
     gc, gs, ge = gpu_out
     idx = torch.from_numpy(rows).cuda()
     gc, gs, ge = gc[idx].cpu().numpy(), gs[idx].cpu().numpy(), ge[idx].cpu().numpy()
-    oc, os_, oe = oracle.quantize(np.ascontiguousarray(x_np[rows]), block, fmt, rec, tensor_scale=T)
+    oc, os_, oe = oracle.quantize(np.ascontiguousarray(x_np[rows]), block, fmt, ORACLE_REC[rec], tensor_scale=T)
     assert (gs == os_).all() and (gc == oc).all()
     assert (ge.view(np.uint32) == oe.view(np.uint32)).all()
 
@@ -289,6 +290,10 @@ def test_config4_brute_full_size_sampled(oracle, mxq):
             check_rows(oracle, x_np, rows, out, block, fmt, 4)
             if fmt == 1:
                 assert bool((out[2] <= f6).all()) and bool((f6 <= ab).all())
+            # the pruned search returns the same bytes as the full enumeration on the whole tensor
+            pr = mxq.quantize(x, block, fmt, 5)
+            torch.cuda.synchronize()
+            assert all(torch.equal(a, b) for a, b in zip(out, pr))
 
 
 def test_config5_layer0_sampled(oracle, mxq):
