@@ -1,0 +1,103 @@
+"""Model-scale sweep: a synthetic 8B-class decoder (32 layers x {q, k, v, o, gate, up, down},
+bf16, 0.02 * Student-t(df=4) with a per-layer, per-matrix seed) quantised with every recipe at
+every block size, one layer resident on the GPU at a time.
+
+    python -m paper_2605_08565_amd.sweep [--layers 32] [--out sweep.json]
+
+Recipes: power-of-two MX (E8M0 abs-max), E4M3 abs-max, E4M3 prevent-zero, E4M3 4-over-6,
+UE5M3 abs-max, E4M3 brute force; block sizes 2 ... 128.  For every (recipe, block size) the
+seven matrices of a layer are quantised back to back (436 MB of input between two touches of
+a matrix, so the 256 MB Infinity Cache does not help) with one event pair around the group.
+Reports GElem/s and the aggregate MSE per (recipe, block size).  Weights are drawn on the GPU
+(this driver measures throughput and quality trends; bit-parity with the CPU oracle is the
+job of the tests, which use the numpy generator of ``workloads``).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+from .workloads import LAYER_SHAPES, N_LAYERS
+
+RECIPES = [("pow2_mx", 0, 0), ("e4m3_absmax", 1, 0), ("e4m3_prevent_zero", 1, 1),
+           ("e4m3_4over6", 1, 2), ("ue5m3_absmax", 2, 0), ("e4m3_brute", 1, 4)]
+BLOCKS = (2, 4, 8, 16, 32, 64, 128)
+
+
+def layer_on_gpu(layer: int, dev):
+    """The seven weight matrices of one layer, drawn on the GPU: 0.02 * Z / sqrt(chi2_4 / 4)."""
+    import torch
+    mats = {}
+    for idx, (name, (r, c)) in enumerate(LAYER_SHAPES.items()):
+        g = torch.Generator(device=dev)
+        g.manual_seed(50_000 + 16 * layer + idx)
+        z = torch.randn((r, c), generator=g, device=dev, dtype=torch.float32)
+        chi = torch.zeros((r, c), device=dev, dtype=torch.float32)
+        for _ in range(4):
+            chi += torch.randn((r, c), generator=g, device=dev, dtype=torch.float32) ** 2
+        mats[name] = (0.02 * z / torch.sqrt(chi / 4.0)).to(torch.bfloat16).contiguous()
+    return mats
+
+
+def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES) -> dict:
+    import torch
+
+    from . import mxq
+
+    dev = torch.device("cuda:0")
+    n_max = max(r * c for r, c in LAYER_SHAPES.values())
+    outs = {name: (torch.empty(r * c // 2, dtype=torch.uint8, device=dev),
+                   torch.empty(r * c // 2, dtype=torch.uint8, device=dev),
+                   torch.empty(r * c // 2, dtype=torch.float32, device=dev))
+            for name, (r, c) in LAYER_SHAPES.items()}
+    del n_max
+    acc = {(rn, b): {"ms": 0.0, "elements": 0, "sse": 0.0} for rn, _, _ in recipes for b in blocks}
+    for layer in range(layers):
+        mats = layer_on_gpu(layer, dev)
+        for x in mats.values():                      # untimed first touch of the new tensors
+            mxq.tensor_absmax(x)
+        torch.cuda.synchronize()
+        for rn, fmt, rec in recipes:
+            for b in blocks:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for name, x in mats.items():
+                    r, c = x.shape
+                    co, so, eo = outs[name]
+                    nb = r * c // b
+                    mxq.quantize(x, b, fmt, rec, codes_out=co.view(r, c // 2),
+                                 scales_out=so[:nb].view(r, c // b), sse_out=eo[:nb].view(r, c // b))
+                e1.record()
+                torch.cuda.synchronize()
+                a = acc[(rn, b)]
+                a["ms"] += e0.elapsed_time(e1)
+                for name, x in mats.items():
+                    a["elements"] += x.numel()
+                    a["sse"] += float(outs[name][2][: x.numel() // b].to(torch.float64).sum())
+        del mats
+    rows = []
+    for (rn, b), a in acc.items():
+        rows.append({"recipe": rn, "block": b, "gelem_s": round(a["elements"] / a["ms"] / 1e6, 1),
+                     "mse": a["sse"] / a["elements"], "elements": a["elements"], "ms": round(a["ms"], 3)})
+    return {"layers": layers, "rows": rows}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--layers", type=int, default=N_LAYERS)
+    ap.add_argument("--out", default="")
+    args = ap.parse_args()
+    res = run(args.layers)
+    text = json.dumps(res)
+    if args.out:
+        with open(args.out, "w") as f:
+            f.write(text)
+    for r in res["rows"]:
+        print(f"{r['recipe']:18s} b={r['block']:<4d} {r['gelem_s']:9.1f} GElem/s   mse {r['mse']:.4e}")
+    if not args.out:
+        sys.stdout.write(text + "\n")
+
+
+if __name__ == "__main__":
+    main()

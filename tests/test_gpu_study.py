@@ -51,3 +51,18 @@ def test_study_regions(result):
             assert (m["brute_force"][b] <= m[r][b] * (1 + 1e-9)).all()
     for lo, hi in ((4, 8), (8, 16), (16, 32)):
         assert (m["brute_force"][lo] <= m["brute_force"][hi] * 1.02).all()
+
+
+def test_model_sweep_driver_one_layer():
+    """The model-scale sweep driver on one layer: every (recipe, block size) runs, MSE trends
+    are the expected ones (brute force lowest; 4-over-6 below abs-max; pow2 floor rule worst)."""
+    from paper_2605_08565_amd import sweep
+    res = sweep.run(layers=1, blocks=(4, 16, 64))
+    mse = {(r["recipe"], r["block"]): r["mse"] for r in res["rows"]}
+    assert len(mse) == 18 and all(v > 0 for v in mse.values())
+    for b in (4, 16, 64):
+        assert mse[("e4m3_brute", b)] <= mse[("e4m3_4over6", b)] <= mse[("e4m3_absmax", b)]
+        assert mse[("e4m3_prevent_zero", b)] <= mse[("e4m3_absmax", b)]
+        assert mse[("pow2_mx", b)] > mse[("e4m3_absmax", b)]
+    assert mse[("e4m3_brute", 4)] < mse[("e4m3_brute", 16)] < mse[("e4m3_brute", 64)]
+    assert all(r["gelem_s"] > 1 for r in res["rows"])
