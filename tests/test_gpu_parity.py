@@ -354,3 +354,84 @@ def test_histogram_full_size(oracle, mxq):
         assert (eh.cpu().numpy().astype(np.uint64) == weh).all()
         assert (sh.cpu().numpy().astype(np.uint64) == wsh).all()
         assert int(eh.sum()) == x_np.size and int(sh.sum()) == x_np.size // block
+
+
+# ------------------------------------------------------------------ graphs, very large tensors
+
+def test_graph_capture_and_replay(oracle, mxq):
+    """The whole path (tensor abs-max, quantise, de-quantise, clip SSE, histogram) captured in
+    a HIP graph and replayed with new input contents between replays, with eager work and
+    synchronisation in between; every replay must equal the oracle on the current contents."""
+    rows, cols, block = 64, 1024, 16
+    x = torch.zeros((rows, cols), dtype=torch.bfloat16, device="cuda")
+    amax = torch.zeros(1, dtype=torch.float32, device="cuda")
+    codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((rows, cols // block), dtype=torch.uint8, device="cuda")
+    sse = torch.empty((rows, cols // block), dtype=torch.float32, device="cuda")
+    deq = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    clip = torch.empty((rows, cols // block), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside capture
+        mxq.quantize(x, block, 1, 2, codes_out=codes, scales_out=scales, sse_out=sse)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        mxq.tensor_absmax(x, out=amax)
+        mxq.quantize(x, block, 1, 2, codes_out=codes, scales_out=scales, sse_out=sse)
+        mxq.dequantize(codes, scales, block, 1, 1.0, out=deq)
+        mxq.clip_sse(x, scales, block, 1, out=clip)
+    for it in range(4):
+        x_np = W.student_t_weights(rows, cols, seed=900 + it)
+        x.copy_(mxq.from_bits(x_np))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        oc, os_, oe = oracle.quantize(x_np, block, 1, 2)
+        assert float(amax.cpu()[0]) == oracle.tensor_absmax(x_np)
+        assert (codes.cpu().numpy() == oc).all() and (scales.cpu().numpy() == os_).all()
+        assert (sse.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
+        want = oracle.dequantize(oc, os_, block, 1, 1.0, oracle.DT_BF16)
+        assert (deq.cpu().view(torch.int16).numpy().view(np.uint16) == want).all()
+        assert (clip.cpu().numpy().view(np.uint32) == oracle.clip_sse(x_np, os_, block, 1).view(np.uint32)).all()
+        # eager work between replays
+        e = mxq.quantize(x, block, 1, 0)[2]
+        assert bool((e >= sse).all())
+
+
+def test_more_than_2_to_32_elements(oracle, mxq):
+    """64-bit indexing: a bf16 tensor of 65 544 x 65 536 = 2^32 + 2^19 elements (8.6 GB).
+    Rows at the start, around the 2^32-element boundary and at the end are checked against the
+    oracle; tensor abs-max against the maximum of the planted values."""
+    rows, cols, block = 65544, 65536, 16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    x = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    step = 4096
+    for r0 in range(0, rows, step):
+        r1 = min(rows, r0 + step)
+        x[r0:r1] = (torch.randn((r1 - r0, cols), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    x[rows - 1, cols - 3] = 7.5
+    x[65536, 5] = -9.25                                 # first row past 2^32 elements
+    torch.cuda.synchronize()
+    print("[large] tensor ready", flush=True)
+    assert float(mxq.tensor_absmax(x).cpu()[0]) == 9.25
+    pick = np.array([0, 1, 32767, 65535, 65536, 65537, rows - 2, rows - 1])
+    idx = torch.from_numpy(pick).cuda()
+    x_np = x[idx].cpu().view(torch.int16).numpy().view(np.uint16)
+    for rec in (0, 2):
+        print(f"[large] recipe {rec}", flush=True)
+        c, s, e = mxq.quantize(x, block, 1, rec)
+        torch.cuda.synchronize()
+        oc, os_, oe = oracle.quantize(x_np, block, 1, rec)
+        assert (c[idx].cpu().numpy() == oc).all() and (s[idx].cpu().numpy() == os_).all()
+        assert (e[idx].cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
+    d = mxq.dequantize(c, s, block, 1, 1.0, torch.bfloat16)
+    torch.cuda.synchronize()
+    want = oracle.dequantize(oc, os_, block, 1, 1.0, oracle.DT_BF16)
+    assert (d[idx].cpu().view(torch.int16).numpy().view(np.uint16) == want).all()
+    eh, sh = mxq.histogram(c, s, block)
+    assert int(eh.sum()) == rows * cols and int(sh.sum()) == rows * cols // block
+    del x, c, s, e, d
+    torch.cuda.empty_cache()
