@@ -94,6 +94,19 @@ def measured_traffic(pass_name):
     return None
 
 
+def measured_valu_busy(pass_name):
+    """VALU-busy percentage of that kernel from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", "valu_counters_bf16_4096x14336.md")
+    kern = KERNEL_OF_PASS.get(pass_name)
+    if kern is None or not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) > 8 and cells[1] == f"`{kern}`":
+            return float(cells[7].rstrip(" %"))
+    return None
+
+
 def cpu_baseline(x_np, passes, T, rows):
     """The oracle, as it stands, on the first `rows` rows of the same tensor, same pass list."""
     import numpy as np
@@ -252,8 +265,11 @@ def main():
             d = {"bound": "alu", "kernel": r["name"], "achieved": r["tflop_s"],
                  "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": r["frac"], "traffic": measured_traffic(r["name"]),
                  "avg_launch_ms": r["ms"],
+                 "frac_of_unpacked_fma_peak": round(r["tflop_s"] / (FP32_VECTOR_PEAK_TFLOPS / 2), 4),
+                 "valu_busy_pct_rocprof": measured_valu_busy(r["name"]),
                  "note": "algorithmic work = 6 flops per (element x candidate): scale, round, residual "
-                         "FMA, square + add; peak is the packed-FMA fp32 vector peak"}
+                         "FMA, square + add; peak is the packed-FMA fp32 vector peak (packed fp32 is "
+                         "not available to this build: the unpacked FMA peak is half of it)"}
         else:
             d = {"bound": "hbm", "kernel": r["name"], "achieved": r["gb_s"], "peak": HBM_PEAK_GBS,
                  "unit": "GB/s", "frac": r["frac"], "traffic": measured_traffic(r["name"]),
