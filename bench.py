@@ -144,7 +144,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-                 "run it with --gpus 1. See DESIGN.md for how the path would shard.")
+                 "run it with --gpus 1 (blocks are independent, so rows shard with no exchange; only the "
+                 "tensor abs-max of hierarchical scaling would need one 4-byte max-all-reduce).")
 
     import numpy as np
     import torch

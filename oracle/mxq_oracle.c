@@ -43,6 +43,9 @@
  * with the SSE accumulated in long double instead; it is used by tests only, to show that
  * the pinned selection differs from the exact one only on near ties.
  *
+ * Besides the path itself the file holds the appendix diagnostic orc_clip_sse (the histograms
+ * are numpy bincounts in the Python wrapper).
+ *
  * Parity pins (tests/, CPU only): the E2M1 value set the paper prints; eps_E4M3 = 2^-9; the
  * closed form of Eq. 1; a library float8 cast for the E4M3 table and its rounding; worked
  * blocks under tests/golden/; exhaustive enumeration on tiny blocks in exact rational
