@@ -118,6 +118,8 @@ __device__ __forceinline__ uint32_t count_mag(uint32_t w, uint32_t k)
     return 8u - (uint32_t)__builtin_popcount(nz);
 }
 
+static_assert(kThreads == 256, "the scale histogram uses one LDS counter per thread");
+
 __global__ void __launch_bounds__(kThreads)
 histogram_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
                  int64_t n_blocks, unsigned long long* __restrict__ elem_hist,
