@@ -16,16 +16,23 @@
 
 namespace mxq {
 
-// Eq. 2 / Eq. 3: scale code from the block abs-max for M = 6 or M = 4.
-template <int FMT, int M>
-__device__ __forceinline__ uint32_t absmax_code(float amax, bool pz)
+// Eq. 2 / Eq. 3: scale codes from the block abs-max for M = 6 and (4-over-6 only) M = 4.
+// `floor_code` is 1 under prevent-zero (eps_SF is code 1 in both formats), else 0.  For E4M3 one
+// v_cvt_pk_fp8_f32 rounds both quotients.
+template <int FMT, bool FOUR6>
+__device__ __forceinline__ void absmax_codes(float amax, uint32_t floor_code, uint32_t& c6, uint32_t& c4)
 {
-    float y;
-    if constexpr (M == 6) y = __builtin_fmaf(amax, kSixthHi, amax * kSixthLo);
-    else y = amax * 0.25f;
-    uint32_t c = sf_encode_rne<FMT>(y);
-    if (pz) c = max(c, 1u);                 // eps_SF is code 1 in both formats
-    return c;
+    const float y6 = __builtin_fmaf(amax, kSixthHi, amax * kSixthLo);
+    const float y4 = amax * 0.25f;
+    if constexpr (FMT == kE4M3) {
+        const float m = ScaleFmt<kE4M3>::kMaxValue;
+        const uint32_t both = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(y6, m), fminf(y4, m), 0, false);
+        c6 = max(both & 0xFFu, floor_code);
+        c4 = FOUR6 ? max((both >> 8) & 0xFFu, floor_code) : 0u;
+    } else {
+        c6 = max(sf_encode_rne<FMT>(y6), floor_code);
+        c4 = FOUR6 ? max(sf_encode_rne<FMT>(y4), floor_code) : 0u;
+    }
 }
 
 // Eq. 1: k = floor(log2(amax / 6)).  With amax = m * 2^e, 1 <= m < 2: k = e - 2 when
@@ -192,22 +199,22 @@ __device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, 
         quant_lane_pow2<NBLK, EPB>(v, code_out, packed, sq);
         block_sse<B>(sq, sse_sel);
     } else {
+        uint32_t c4[NBLK];
+        const uint32_t floor_code = pz ? 1u : 0u;
 #pragma unroll
-        for (int k = 0; k < NBLK; ++k) code_out[k] = absmax_code<FMT, 6>(amax[k], pz);
+        for (int k = 0; k < NBLK; ++k) absmax_codes<FMT, FOUR6>(amax[k], floor_code, code_out[k], c4[k]);
         quant_lane<NBLK, EPB>(v, code_out, tab, packed, sq);
         block_sse<B>(sq, sse_sel);
         if constexpr (FOUR6) {
-            uint32_t c4[NBLK], packed4;
+            uint32_t packed4;
             float sse4[4];
-#pragma unroll
-            for (int k = 0; k < NBLK; ++k) c4[k] = absmax_code<FMT, 4>(amax[k], pz);
             quant_lane<NBLK, EPB>(v, c4, tab, packed4, sq);
             block_sse<B>(sq, sse4);
             // Eq. 4: M = 4 only when its SSE is strictly lower
 #pragma unroll
             for (int k = 0; k < NBLK; ++k) {
                 if (sse4[k] < sse_sel[k]) {
-                    constexpr uint32_t m = (EPB == 8) ? 0xFFFFFFFFu : ((1u << (4 * EPB)) - 1u);
+                    constexpr uint32_t m = (EPB == 8) ? 0xFFFFFFFFu : ((1u << ((4 * EPB) & 31)) - 1u);
                     const uint32_t mask = m << ((4 * EPB * k) & 31);
                     packed = (packed & ~mask) | (packed4 & mask);
                     code_out[k] = c4[k];
