@@ -99,7 +99,7 @@ typedef enum { MXQ_DT_BF16 = 0, MXQ_DT_F32 = 1 } mxq_dtype;
  *
  * rows*cols == 0 is a valid no-op.  Errors: INVALID_ARG (NULL x/codes_out/scales_out,
  * negative size, bad block, cols % block != 0, unknown enum, tensor_scale not finite or
- * <= 0), UNSUPPORTED (see mxq_recipe), ALIGNMENT, HIP.
+ * <= 0), UNSUPPORTED (see mxq_recipe; rows*cols >= 2^42), ALIGNMENT, HIP.
  */
 MXQ_API int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
                  int elem_fmt, int scale_fmt, int recipe, float tensor_scale,

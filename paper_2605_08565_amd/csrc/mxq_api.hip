@@ -49,6 +49,7 @@ int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
     if (scale_fmt == MXQ_SCALE_E8M0 && recipe >= MXQ_RECIPE_4OVER6) return MXQ_ERR_UNSUPPORTED;
     const int64_t n = rows * cols;
     if (n == 0) return MXQ_OK;
+    if (n >= ((int64_t)1 << 42)) return MXQ_ERR_UNSUPPORTED;        // 32-bit slice counters
     if (!x || !codes_out || !scales_out) return MXQ_ERR_INVALID_ARG;
     if (!aligned(x, 16) || !aligned(codes_out, 4) || !aligned(scales_out, 4) ||
         (sse_out && !aligned(sse_out, 16)))

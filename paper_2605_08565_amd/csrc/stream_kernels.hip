@@ -266,19 +266,27 @@ struct TileOut {
     float sse[4];
 };
 
-// Stores of one slice (256 chunks starting at chunk c0, a multiple of 256).  All slice
-// arithmetic is wave-uniform: addresses are a scalar base plus a 32-bit lane offset.
+// The complete chunks are cut into slices of 256 chunks (one chunk per lane).  Slice indices
+// are 32-bit and wave-uniform, so all tile arithmetic runs on the scalar unit and every address
+// is a scalar base plus a 32-bit lane offset.
+struct Slices {
+    uint32_t count;        // number of slices
+    uint32_t last;         // chunks in the last slice, 1 .. 256
+    __device__ __forceinline__ uint32_t chunks(uint32_t s) const { return (s + 1u == count) ? last : (uint32_t)kThreads; }
+};
+
+// Stores of one slice.
 template <int B>
-__device__ __forceinline__ void store_slice(const TileOut<B>& o, int64_t c0, int64_t n_full,
+__device__ __forceinline__ void store_slice(const TileOut<B>& o, uint32_t s, Slices sl,
                                             uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
                                             float* __restrict__ sse_out)
 {
     constexpr int NBLK = TileOut<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
     const uint32_t tid = threadIdx.x;
-    if (c0 >= n_full) return;                                        // uniform
-    const uint32_t here = (uint32_t)min((int64_t)kThreads, n_full - c0);
-    if (tid < here) {
+    if (s >= sl.count) return;                                       // uniform
+    const uint64_t c0 = (uint64_t)s * kThreads;                      // first chunk of the slice
+    if (tid < sl.chunks(s)) {
         __builtin_nontemporal_store(o.packed, codes + c0 + tid);
         if constexpr (B >= 8) {
             if ((tid & (LANES - 1)) == 0) {
@@ -299,27 +307,25 @@ __device__ __forceinline__ void store_slice(const TileOut<B>& o, int64_t c0, int
     }
 }
 
-// A workgroup tile is kItems slices of 256 chunks; every lane owns one chunk of each slice.
+// A workgroup tile is kItems consecutive slices; every lane owns one chunk of each slice.
 constexpr int kItems = MXQ_STREAM_ITEMS;
-constexpr int64_t kTileChunks = (int64_t)kThreads * kItems;
 
 template <int DT>
 __device__ __forceinline__ void load_tile(RawChunk<DT> (&buf)[kItems], const void* __restrict__ x,
-                                          int64_t c0, int64_t n_full)
+                                          uint32_t s0, Slices sl)
 {
-    constexpr int64_t kVecPerChunk = (DT == kBF16) ? 1 : 2;
+    constexpr uint64_t kVecPerChunk = (DT == kBF16) ? 1 : 2;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        const int64_t ci = c0 + (int64_t)i * kThreads;
-        if (ci < n_full) {                                           // uniform
-            const uint32_t left = (uint32_t)min((int64_t)kThreads, n_full - ci);
-            buf[i] = load_raw<DT>(static_cast<const u32x4*>(x) + ci * kVecPerChunk,
-                                  min((uint32_t)threadIdx.x, left - 1u));
+        const uint32_t s = s0 + (uint32_t)i;
+        if (s < sl.count) {                                          // uniform
+            buf[i] = load_raw<DT>(static_cast<const u32x4*>(x) + (uint64_t)s * kThreads * kVecPerChunk,
+                                  min((uint32_t)threadIdx.x, sl.chunks(s) - 1u));
         }
     }
 }
 
-// One step of the software pipeline for the tile at c0 whose raw data sits in `cur`:
+// One step of the software pipeline for the tile at slice s0 whose raw data sits in `cur`:
 //   wait until `cur` has landed -> issue the stores of the PREVIOUS tile -> issue the loads of
 //   the NEXT tile into `nxt` -> quantise `cur` into `out`.
 // On gfx9 loads and stores share one in-order counter, so the wait at the top covers every
@@ -327,9 +333,9 @@ __device__ __forceinline__ void load_tile(RawChunk<DT> (&buf)[kItems], const voi
 // phase earlier and the wait is short.
 template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChunk<DT> (&nxt)[kItems],
-                                            TileOut<B> (&out)[kItems], bool have_prev, int64_t c_prev,
-                                            const void* __restrict__ x, int64_t c0, int64_t stride,
-                                            int64_t n_full, float T, float rT, bool pz, const ScaleEntry* tab,
+                                            TileOut<B> (&out)[kItems], bool have_prev, uint32_t s_prev,
+                                            const void* __restrict__ x, uint32_t s0, uint32_t stride,
+                                            Slices sl, float T, float rT, bool pz, const ScaleEntry* tab,
                                             uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
                                             float* __restrict__ sse_out)
 {
@@ -340,54 +346,53 @@ __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChun
     __builtin_amdgcn_sched_barrier(0);
     if (have_prev) {                                                 // uniform
 #pragma unroll
-        for (int i = 0; i < kItems; ++i)
-            store_slice<B>(out[i], c_prev + (int64_t)i * kThreads, n_full, codes, scales, sse_out);
+        for (int i = 0; i < kItems; ++i) store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out);
     }
-    if (c0 + stride < n_full) load_tile<DT>(nxt, x, c0 + stride, n_full);      // uniform
+    if (s0 + stride < sl.count) load_tile<DT>(nxt, x, s0 + stride, sl);            // uniform
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kItems; ++i)
         process_chunk<B, FMT, FOUR6, TMODE>(v[i], T, rT, pz, tab, out[i].packed, out[i].code, out[i].sse);
 }
 
-// Main kernel: the n_full = n / 8 complete chunks, grid-stride over workgroup tiles with two
-// register buffers alternating between "being processed" and "in flight".
+// Main kernel: the complete chunks, grid-stride over workgroup tiles with two register buffers
+// alternating between "being processed" and "in flight".
 template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __global__ void __launch_bounds__(kThreads)
-stream_kernel(const void* __restrict__ x, int64_t n_full, float T, int pz,
+stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunks, float T, int pz,
               uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
     if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
 
-    const int64_t stride = (int64_t)gridDim.x * kTileChunks;
-    int64_t c0 = (int64_t)blockIdx.x * kTileChunks;
-    if (c0 >= n_full) return;
+    const Slices sl{n_slices, last_chunks};
+    const uint32_t stride = gridDim.x * (uint32_t)kItems;
+    uint32_t s0 = blockIdx.x * (uint32_t)kItems;
+    if (s0 >= sl.count) return;
     const float rT = 1.0f / T;                                       // correctly rounded
 
     RawChunk<DT> bufA[kItems], bufB[kItems];
 #pragma unroll
     for (int i = 0; i < kItems; ++i) { bufA[i] = RawChunk<DT>{}; bufB[i] = RawChunk<DT>{}; }
-    load_tile<DT>(bufA, x, c0, n_full);
+    load_tile<DT>(bufA, x, s0, sl);
     TileOut<B> out[kItems];
     bool have_prev = false;
-    int64_t c_prev = c0;
+    uint32_t s_prev = s0;
     while (true) {
-        stream_step<DT, B, FMT, FOUR6, TMODE>(bufA, bufB, out, have_prev, c_prev, x, c0, stride, n_full,
+        stream_step<DT, B, FMT, FOUR6, TMODE>(bufA, bufB, out, have_prev, s_prev, x, s0, stride, sl,
                                               T, rT, pz != 0, tab, codes, scales, sse_out);
         have_prev = true;
-        c_prev = c0;
-        c0 += stride;
-        if (c0 >= n_full) break;
-        stream_step<DT, B, FMT, FOUR6, TMODE>(bufB, bufA, out, true, c_prev, x, c0, stride, n_full,
+        s_prev = s0;
+        s0 += stride;
+        if (s0 >= sl.count) break;
+        stream_step<DT, B, FMT, FOUR6, TMODE>(bufB, bufA, out, true, s_prev, x, s0, stride, sl,
                                               T, rT, pz != 0, tab, codes, scales, sse_out);
-        c_prev = c0;
-        c0 += stride;
-        if (c0 >= n_full) break;
+        s_prev = s0;
+        s0 += stride;
+        if (s0 >= sl.count) break;
     }
 #pragma unroll
-    for (int i = 0; i < kItems; ++i)
-        store_slice<B>(out[i], c_prev + (int64_t)i * kThreads, n_full, codes, scales, sse_out);
+    for (int i = 0; i < kItems; ++i) store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out);
 }
 
 // Ragged tail: when n is not a multiple of 8 (only possible for b = 2 or 4) the last
@@ -431,17 +436,20 @@ static hipError_t launch_recipe(const StreamArgs& a, int pz)
     const bool fast_t = a.T >= 0x1p-20f && a.T <= 0x1p20f && (tb & 0x7FFFFFu) != 0x7FFFFFu;
     const int tmode = (a.T == 1.0f) ? kNoT : (fast_t ? kFastT : kSlowT);
     if (n_full > 0) {
-        const dim3 grid(stream_grid((n_full + kItems - 1) / kItems)), block(kThreads);
+        const int64_t slices = (n_full + kThreads - 1) / kThreads;
+        const uint32_t n_slices = (uint32_t)slices;
+        const uint32_t last = (uint32_t)(n_full - (slices - 1) * kThreads);
+        const dim3 grid(stream_grid(((slices + kItems - 1) / kItems) * kThreads)), block(kThreads);
         uint32_t* codes = reinterpret_cast<uint32_t*>(a.codes);
         if (tmode == kNoT)
             hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kNoT>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, pz, codes, a.scales, a.sse);
+                               a.x, n_slices, last, a.T, pz, codes, a.scales, a.sse);
         else if (tmode == kFastT)
             hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kFastT>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, pz, codes, a.scales, a.sse);
+                               a.x, n_slices, last, a.T, pz, codes, a.scales, a.sse);
         else
             hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kSlowT>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, pz, codes, a.scales, a.sse);
+                               a.x, n_slices, last, a.T, pz, codes, a.scales, a.sse);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
