@@ -341,3 +341,24 @@ def test_4over6_moves_mass_from_bin_6_to_bin_4(oracle):
         return np.bincount(mags, minlength=8)
     h0, h2 = hist(0), hist(2)
     assert h2[7] < h0[7] and h2[6] > h0[6]
+
+
+def test_hierarchical_scale_and_ue5m3_are_interchangeable(oracle):
+    """Section 3.2, on MSE instead of perplexity: for small-magnitude tensors E4M3 alone loses
+    accuracy (its scales sit in the coarse sub-normal range or underflow); a per-tensor scale or
+    the wider UE5M3 range both repair it, to the same level; a per-tensor scale on top of UE5M3
+    changes nothing; 4-over-6 helps on top of either."""
+    x = W.normal_f32(256, 512, seed=97, sigma=0.003)
+    n = x.size
+
+    def mse(fmt, rec, H):
+        T = oracle.tensor_scale(oracle.tensor_absmax(x), fmt) if H else 1.0
+        return oracle.tensor_mse(oracle.quantize(x, 8, fmt, rec, tensor_scale=T)[2], n, T)
+
+    e4, e4h = mse(1, 0, False), mse(1, 0, True)
+    u5, u5h = mse(2, 0, False), mse(2, 0, True)
+    assert e4 > 5 * e4h and e4 > 5 * u5                      # E4M3 alone is much worse here
+    assert 0.8 < e4h / u5 < 1.25                             # H and UE5M3: comparable
+    assert 0.9 < u5h / u5 < 1.1                              # H adds nothing on top of UE5M3
+    assert mse(1, 2, True) < 0.9 * e4h and mse(2, 2, False) < 0.9 * u5     # separate effect of 4-over-6
+    assert 0.8 < mse(1, 2, True) / mse(2, 2, False) < 1.25
