@@ -32,11 +32,39 @@ struct BruteState {
     uint32_t best_code[NBLK];
 };
 
-// SSE of the lane's blocks under S = mant_value(MI) * scale2 (scale2 a power of two), and the
-// running arg-min.  w holds the lane's quotients v / mant_value(MI).
-template <int B, int MI>
+// Arg-min inside one group of up to 8 consecutive codes: the running minimum and the position
+// (0..7, 8 = none yet) of the first candidate of the group that improved on it.  The position is
+// an inline constant of the select instruction, so a candidate costs compare + two selects.
+template <int B>
+struct GroupBest {
+    static constexpr int NBLK = BruteState<B>::NBLK;
+    float sse[NBLK];
+    uint32_t pos[NBLK];
+};
+
+template <int B>
+__device__ __forceinline__ void group_begin(const BruteState<B>& st, GroupBest<B>& g)
+{
+#pragma unroll
+    for (int k = 0; k < GroupBest<B>::NBLK; ++k) { g.sse[k] = st.best_sse[k]; g.pos[k] = 8u; }
+}
+
+// code of position p in the group is code0 + p
+template <int B>
+__device__ __forceinline__ void group_end(BruteState<B>& st, const GroupBest<B>& g, uint32_t code0)
+{
+#pragma unroll
+    for (int k = 0; k < GroupBest<B>::NBLK; ++k) {
+        st.best_code[k] = (g.pos[k] != 8u) ? code0 + g.pos[k] : st.best_code[k];
+        st.best_sse[k] = g.sse[k];
+    }
+}
+
+// SSE of the lane's blocks under S = mant_value(MI) * scale2 (scale2 a power of two), entered
+// into the group's arg-min at position POS.  w holds the lane's quotients v / mant_value(MI).
+template <int B, int MI, int POS>
 __device__ __forceinline__ void try_candidate(const float (&v)[8], const float (&w)[8], float scale2,
-                                              uint32_t code, BruteState<B>& st)
+                                              GroupBest<B>& g)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     const uint32_t packed = e2m1_pack8(w, scale2);
@@ -60,21 +88,32 @@ __device__ __forceinline__ void try_candidate(const float (&v)[8], const float (
     }
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
-        const bool better = s[k] < st.best_sse[k];
-        st.best_sse[k] = better ? s[k] : st.best_sse[k];
-        st.best_code[k] = better ? code : st.best_code[k];
+        const bool better = s[k] < g.sse[k];                           // strict: ties keep the lower code
+        g.sse[k] = better ? s[k] : g.sse[k];
+        g.pos[k] = better ? (uint32_t)POS : g.pos[k];
     }
 }
 
 template <int B, int FMT, int MI>
-__device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)[8][8], float scale2,
-                                           uint32_t code0, BruteState<B>& st)
+__device__ __forceinline__ void try_binade_from(const float (&v)[8], const float (&w)[8][8], float scale2,
+                                                uint32_t code0, GroupBest<B>& g)
 {
     if constexpr (MI < 8) {
         if (code0 + MI <= (uint32_t)ScaleFmt<FMT>::kMaxCode)            // skips the NaN code only
-            try_candidate<B, MI>(v, w[MI], scale2, code0 + MI, st);
-        try_binade<B, FMT, MI + 1>(v, w, scale2, code0, st);
+            try_candidate<B, MI, MI>(v, w[MI], scale2, g);
+        try_binade_from<B, FMT, MI + 1>(v, w, scale2, code0, g);
     }
+}
+
+// The 8 codes code0 .. code0 + 7 of one binade: (1 + mi/8) * scale2.
+template <int B, int FMT>
+__device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)[8][8], float scale2,
+                                           uint32_t code0, BruteState<B>& st)
+{
+    GroupBest<B> g;
+    group_begin<B>(st, g);
+    try_binade_from<B, FMT, 0>(v, w, scale2, code0, g);
+    group_end<B>(st, g, code0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -182,19 +221,22 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
     const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
     const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
     if (lo_w < 8u) {                                                    // uniform
-        try_candidate<B, 0>(v, w[0], s1, 1u, st);
-        try_candidate<B, 0>(v, w[0], s2, 2u, st);
-        try_candidate<B, 4>(v, w[4], s2, 3u, st);
-        try_candidate<B, 0>(v, w[0], s4, 4u, st);
-        try_candidate<B, 2>(v, w[2], s4, 5u, st);
-        try_candidate<B, 4>(v, w[4], s4, 6u, st);
-        try_candidate<B, 6>(v, w[6], s4, 7u, st);
+        GroupBest<B> g;
+        group_begin<B>(st, g);
+        try_candidate<B, 0, 0>(v, w[0], s1, g);
+        try_candidate<B, 0, 1>(v, w[0], s2, g);
+        try_candidate<B, 4, 2>(v, w[4], s2, g);
+        try_candidate<B, 0, 3>(v, w[0], s4, g);
+        try_candidate<B, 2, 4>(v, w[2], s4, g);
+        try_candidate<B, 4, 5>(v, w[4], s4, g);
+        try_candidate<B, 6, 6>(v, w[6], s4, g);
+        group_end<B>(st, g, 1u);
     }
 
     // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
     for (uint32_t ef = max(lo_w >> 3, 1u); ef <= (hi_w >> 3); ++ef) {
         const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
-        try_binade<B, FMT, 0>(v, w, scale2, ef << 3, st);
+        try_binade<B, FMT>(v, w, scale2, ef << 3, st);
     }
 
     // codes of the winners

@@ -150,10 +150,13 @@ __device__ __forceinline__ void e2m1_unpack2(uint32_t packed, float scale, float
     b = r.y;
 }
 
-// 8 values -> one dword of codes (element j in nibble j).
+// 8 values -> one dword of codes (element j in nibble j).  The four conversions overwrite all
+// four bytes, so the register they accumulate into needs no initial value; the empty asm
+// statement defines it without emitting an instruction.
 __device__ __forceinline__ uint32_t e2m1_pack8(const float (&y)[8], float scale)
 {
-    uint32_t r = 0u;
+    uint32_t r;
+    asm volatile("" : "=v"(r));
     r = e2m1_pack2<0>(r, y[0], y[1], scale);
     r = e2m1_pack2<1>(r, y[2], y[3], scale);
     r = e2m1_pack2<2>(r, y[4], y[5], scale);
