@@ -5,17 +5,6 @@
 
 namespace mxq {
 
-__device__ __forceinline__ float scale_value_any(int fmt, uint32_t code)
-{
-    const float nan = u2f(0x7FC00000u);
-    if (fmt == kE8M0) {
-        if (code == 255u) return nan;
-        return (code == 0u) ? u2f(0x00400000u) : u2f(code << 23);
-    }
-    if (fmt == kE4M3) return (code > (uint32_t)ScaleFmt<kE4M3>::kMaxCode) ? nan : sf_decode<kE4M3>(code);
-    return (code > (uint32_t)ScaleFmt<kUE5M3>::kMaxCode) ? nan : sf_decode<kUE5M3>(code);
-}
-
 using bf16x2 = __bf16 __attribute__((ext_vector_type(2)));
 
 // Two fp32 -> two bf16 (round to nearest even, v_cvt_pk_bf16_f32), first value in the low half.
@@ -54,7 +43,7 @@ dequant_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ s
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) {
             const int64_t blk = (B >= 8) ? chunk / LANES : chunk * NBLK + k;
-            S[k] = (B >= 8 || k < count / B) ? scale_value_any(fmt, scales[blk]) : 0.0f;
+            S[k] = (B >= 8 || k < count / B) ? scale_byte_value(fmt, scales[blk]) : 0.0f;
         }
         float r[8];
         e2m1_unpack8(packed, 1.0f, r);

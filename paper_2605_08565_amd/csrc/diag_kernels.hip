@@ -6,17 +6,6 @@
 
 namespace mxq {
 
-__device__ __forceinline__ float diag_scale_value(int fmt, uint32_t code)
-{
-    const float nan = u2f(0x7FC00000u);
-    if (fmt == kE8M0) {
-        if (code == 255u) return nan;
-        return (code == 0u) ? u2f(0x00400000u) : u2f(code << 23);
-    }
-    if (fmt == kE4M3) return (code > (uint32_t)ScaleFmt<kE4M3>::kMaxCode) ? nan : sf_decode<kE4M3>(code);
-    return (code > (uint32_t)ScaleFmt<kUE5M3>::kMaxCode) ? nan : sf_decode<kUE5M3>(code);
-}
-
 // One lane = 8 consecutive elements.  An element clips when fl32(|v| / S) > 6, which for the
 // short significands of S is the same as |v| > 6 * S (6 * S is exact); its residual is
 // v - (+-6) * S, one FMA because the product is exact.
@@ -45,7 +34,7 @@ clip_sse_kernel(const void* __restrict__ x, const uint8_t* __restrict__ scales, 
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) {
             float S = 0.0f;
-            if (k * EPB < count) S = diag_scale_value(fmt, scales[(B >= 8) ? chunk / LANES : chunk * NBLK + k]);
+            if (k * EPB < count) S = scale_byte_value(fmt, scales[(B >= 8) ? chunk / LANES : chunk * NBLK + k]);
             const float lim = 6.0f * S;
 #pragma unroll
             for (int i = 0; i < EPB; ++i) {

@@ -65,6 +65,19 @@ __device__ __forceinline__ uint32_t sf_encode_rne(float y)
     return (y < min_normal) ? sub : nrm;
 }
 
+// Value of any scale byte of any format (NaN for bytes that are not finite numbers); used where
+// the format is a run-time argument (de-quantise, diagnostics).
+__device__ __forceinline__ float scale_byte_value(int fmt, uint32_t code)
+{
+    const float nan = u2f(0x7FC00000u);
+    if (fmt == kE8M0) {
+        if (code == 255u) return nan;
+        return (code == 0u) ? u2f(0x00400000u) : u2f(code << 23);      // 2^-127 is sub-normal
+    }
+    if (fmt == kE4M3) return (code > (uint32_t)ScaleFmt<kE4M3>::kMaxCode) ? nan : sf_decode<kE4M3>(code);
+    return (code > (uint32_t)ScaleFmt<kUE5M3>::kMaxCode) ? nan : sf_decode<kUE5M3>(code);
+}
+
 // ---------------------------------------------------------------------------------------
 // Quotients whose rounding decisions are exact.
 //
@@ -170,14 +183,6 @@ __device__ __forceinline__ void e2m1_unpack8(uint32_t packed, float scale, float
     e2m1_unpack2<1>(packed, scale, q[2], q[3]);
     e2m1_unpack2<2>(packed, scale, q[4], q[5]);
     e2m1_unpack2<3>(packed, scale, q[6], q[7]);
-}
-
-// Value of a magnitude index: 0, 0.5, then (1 + m/2) * 2^(e-1) as fp32 bits.
-__device__ __forceinline__ float e2m1_mag_value(uint32_t mag)
-{
-    const float lowv = 0.5f * (float)mag;
-    const float high = u2f((mag + 252u) << 22);
-    return (mag < 2u) ? lowv : high;
 }
 
 // ---------------------------------------------------------------------------------------
