@@ -75,7 +75,7 @@ KERNEL_OF_PASS = {   # pass name -> kernel instantiation, as rocprofv3 prints it
     "absmax_e4m3_b16_H": "mxq::stream_kernel<0, 16, 1, false, 1>",
     "brute_e4m3_b16": "mxq::brute_kernel<0, 16, 1, false, false>",
     "brute_ue5m3_b16": "mxq::brute_kernel<0, 16, 2, false, false>",
-    "dequantize_e4m3_b16_bf16": "mxq::dequant_kernel<0, 16>",
+    "dequantize_e4m3_b16_bf16": "mxq::dequant_bf16_kernel<16>",
     "tensor_absmax": "mxq::absmax_kernel<0>",
 }
 

@@ -14,12 +14,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// One lane = 8 consecutive elements = one dword of codes; a block of b >= 8 elements spans
-// b/8 lanes that all read the same scale byte, a block of b < 8 lies inside the lane.
-template <int DT, int B>
+// bf16 output: one lane = 8 consecutive elements = one dword of codes = one 128-bit store; a
+// block of b >= 8 elements spans b/8 lanes that all read the same scale byte, a block of b < 8
+// lies inside the lane.
+template <int B>
 __global__ void __launch_bounds__(kThreads)
-dequant_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
-               int fmt, float T, void* __restrict__ out)
+dequant_bf16_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
+                    int fmt, float T, uint16_t* __restrict__ out)
 {
     constexpr int NBLK = (B < 8) ? 8 / B : 1;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
@@ -50,37 +51,83 @@ dequant_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ s
 #pragma unroll
         for (int i = 0; i < 8; ++i) r[i] = (r[i] * S[i / EPB]) * T;
         if (count == 8) {
-            if constexpr (DT == kBF16) {
-                u32x4 o;
-                o.x = pack_bf16x2(r[0], r[1]);
-                o.y = pack_bf16x2(r[2], r[3]);
-                o.z = pack_bf16x2(r[4], r[5]);
-                o.w = pack_bf16x2(r[6], r[7]);
-                __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(out) + first));
-            } else {
-                u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(out) + first);
-                const u32x4 lo = {f2u(r[0]), f2u(r[1]), f2u(r[2]), f2u(r[3])};
-                const u32x4 hi = {f2u(r[4]), f2u(r[5]), f2u(r[6]), f2u(r[7])};
-                __builtin_nontemporal_store(lo, p);
-                __builtin_nontemporal_store(hi, p + 1);
-            }
+            u32x4 o;
+            o.x = pack_bf16x2(r[0], r[1]);
+            o.y = pack_bf16x2(r[2], r[3]);
+            o.z = pack_bf16x2(r[4], r[5]);
+            o.w = pack_bf16x2(r[6], r[7]);
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out + first));
         } else {
-            for (int i = 0; i < count; ++i) {
-                if constexpr (DT == kBF16)
-                    static_cast<uint16_t*>(out)[first + i] = (uint16_t)(pack_bf16x2(r[i], 0.0f) & 0xFFFFu);
-                else
-                    static_cast<float*>(out)[first + i] = r[i];
-            }
+            for (int i = 0; i < count; ++i) out[first + i] = (uint16_t)(pack_bf16x2(r[i], 0.0f) & 0xFFFFu);
         }
     }
 }
 
-template <int DT>
-static void launch_dequant_dt(const DequantArgs& a, int grid)
+// fp32 output: one lane = 4 consecutive elements = 16 bits of codes = one 128-bit store, so a
+// store instruction of a wavefront covers 1 KiB without gaps (with 8 elements per lane its two
+// stores would each leave every other 16 bytes untouched).  n is even, so the ragged last lane
+// holds 2 elements.
+template <int B>
+__global__ void __launch_bounds__(kThreads)
+dequant_f32_kernel(const uint16_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
+                   int fmt, float T, float* __restrict__ out)
 {
+    constexpr int NBLK = (B < 4) ? 4 / B : 1;
+    constexpr int EPB = (B < 4) ? B : 4;
+    const int64_t n_half = (n + 3) >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t h0 = (int64_t)blockIdx.x * kThreads; h0 < n_half; h0 += stride) {       // uniform
+        const uint32_t tid = threadIdx.x;
+        if (tid >= (uint32_t)min((int64_t)kThreads, n_half - h0)) continue;
+        const int64_t h = h0 + tid;
+        const int64_t first = h << 2;
+        const int count = (int)min((int64_t)4, n - first);
+        const uint32_t packed = (count == 4) ? (uint32_t)__builtin_nontemporal_load(codes + h)
+                                             : (uint32_t)reinterpret_cast<const uint8_t*>(codes)[h * 2];
+        float S[NBLK];
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) {
+            const int64_t blk = (B >= 4) ? first / B : h * NBLK + k;
+            S[k] = (B >= 4 || k < count / B) ? scale_byte_value(fmt, scales[blk]) : 0.0f;
+        }
+        float r[4];
+        e2m1_unpack2<0>(packed, 1.0f, r[0], r[1]);
+        e2m1_unpack2<1>(packed, 1.0f, r[2], r[3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (r[i] * S[i / EPB]) * T;
+        if (count == 4) {
+            const u32x4 o = {f2u(r[0]), f2u(r[1]), f2u(r[2]), f2u(r[3])};
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(out + first));
+        } else {
+            for (int i = 0; i < count; ++i) out[first + i] = r[i];
+        }
+    }
+}
+
+static void launch_dequant_f32(const DequantArgs& a)
+{
+    const int grid = stream_grid((a.n + 3) / 4);
+#define MXQ_DQF(BB)                                                                                  \
+    hipLaunchKernelGGL((dequant_f32_kernel<BB>), dim3(grid), dim3(kThreads), 0, a.stream,           \
+                       (const uint16_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, (float*)a.out)
+    switch (a.block) {
+        case 2: MXQ_DQF(2); break;
+        case 4: MXQ_DQF(4); break;
+        case 8: MXQ_DQF(8); break;
+        case 16: MXQ_DQF(16); break;
+        case 32: MXQ_DQF(32); break;
+        case 64: MXQ_DQF(64); break;
+        default: MXQ_DQF(128); break;
+    }
+#undef MXQ_DQF
+}
+
+static void launch_dequant_bf16(const DequantArgs& a)
+{
+    const int grid = stream_grid((a.n + 7) / 8);
 #define MXQ_DQ(BB)                                                                                   \
-    hipLaunchKernelGGL((dequant_kernel<DT, BB>), dim3(grid), dim3(kThreads), 0, a.stream,           \
-                       (const uint32_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, a.out)
+    hipLaunchKernelGGL((dequant_bf16_kernel<BB>), dim3(grid), dim3(kThreads), 0, a.stream,          \
+                       (const uint32_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, (uint16_t*)a.out)
     switch (a.block) {
         case 2: MXQ_DQ(2); break;
         case 4: MXQ_DQ(4); break;
@@ -95,10 +142,8 @@ static void launch_dequant_dt(const DequantArgs& a, int grid)
 
 hipError_t launch_dequant(const DequantArgs& a)
 {
-    const int64_t n_chunks = (a.n + 7) / 8;
-    const int grid = stream_grid(n_chunks);
-    if (a.dtype == kBF16) launch_dequant_dt<kBF16>(a, grid);
-    else launch_dequant_dt<kF32>(a, grid);
+    if (a.dtype == kBF16) launch_dequant_bf16(a);
+    else launch_dequant_f32(a);
     return hipGetLastError();
 }
 

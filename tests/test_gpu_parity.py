@@ -209,6 +209,25 @@ def test_dequantize(oracle, mxq, block):
                     assert (g == want).all()
 
 
+@pytest.mark.parametrize("block", (2, 4, 8, 16, 32, 64, 128))
+def test_dequantize_ragged_and_multi_pass(oracle, mxq, block):
+    """Element counts that leave a partial lane (fp32 output: 4 elements per lane, bf16: 8) and a
+    tensor large enough that the fp32 kernel's grid-stride loop runs more than once."""
+    rng = np.random.default_rng(100 + block)
+    shapes = [(3, block * (3 if block < 8 else 1)), (1, block), (1536, 2048)]
+    for rows, cols in shapes:
+        codes = rng.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)
+        scales = rng.integers(0, 0x7F, size=(rows, cols // block), dtype=np.uint8)
+        for dt, tdt in ((oracle.DT_F32, torch.float32), (oracle.DT_BF16, torch.bfloat16)):
+            want = oracle.dequantize(codes, scales, block, 1, 0.37, dt)
+            got = mxq.dequantize(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(),
+                                 block, 1, 0.37, tdt).cpu()
+            if tdt == torch.float32:
+                assert (got.numpy().view(np.uint32) == want.view(np.uint32)).all(), (rows, cols)
+            else:
+                assert (got.view(torch.int16).numpy().view(np.uint16) == want).all(), (rows, cols)
+
+
 def test_dequantize_roundtrip_ragged(oracle, mxq):
     x = W.student_t_weights(5, 12, seed=8)
     c, s, _ = oracle.quantize(x, 4, 1, 0)
