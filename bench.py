@@ -75,6 +75,8 @@ KERNEL_OF_PASS = {   # pass name -> kernel instantiation, as rocprofv3 prints it
     "absmax_e4m3_b16_H": "mxq::stream_kernel<0, 16, 1, false, 1>",
     "brute_e4m3_b16": "mxq::brute_kernel<0, 16, 1, false, false>",
     "brute_ue5m3_b16": "mxq::brute_kernel<0, 16, 2, false, false>",
+    "brute_e4m3_b4": "mxq::brute_kernel<0, 4, 1, false, false>",
+    "brute_ue5m3_b4": "mxq::brute_kernel<0, 4, 2, false, false>",
     "dequantize_e4m3_b16_bf16": "mxq::dequant_bf16_kernel<16>",
     "tensor_absmax": "mxq::absmax_kernel<0>",
 }
@@ -279,7 +281,9 @@ def main():
             d.update(extra)
         return d
 
-    dom = max(kern, key=lambda r: r["ms"])
+    # dominant kernel: the launch with the most algorithmic work (254 candidates); b=16 and b=4
+    # take the same time within run-to-run noise, so the choice between them is fixed, not timed
+    dom = next((r for r in kern if r["name"] == "brute_ue5m3_b16"), max(kern, key=lambda r: r["ms"]))
     out = {
         "metric": "GElem/s quantized per recipe (absmax, 4-over-6, brute-force); % HBM/VALU roof",
         "value": round(value, 3), "unit": "GElem/s", "n_gpus": 1, "steps": args.steps,

@@ -229,22 +229,32 @@ template <int DT> struct RawChunk;
 template <> struct RawChunk<kBF16> { u32x4 a; };
 template <> struct RawChunk<kF32> { u32x4 a, b; };
 
-// `tile` points at the workgroup's 256 chunks (wave-uniform), `lane` is the chunk inside it.
+// `tile` points at the workgroup's 256 chunks (wave-uniform), `tid` is the lane's chunk inside
+// it and `chunks` the number of valid chunks (lanes beyond them re-read the last valid data).
+// bf16: one 128-bit load per lane.  fp32: a chunk is two 128-bit vectors; so that every load
+// instruction of a wavefront covers 1 KiB without gaps, lane l of wave w reads vectors
+// 128w + l and 128w + 64 + l, and widen() below hands every lane its own chunk through LDS.
 template <int DT>
-__device__ __forceinline__ RawChunk<DT> load_raw(const u32x4* __restrict__ tile, uint32_t lane)
+__device__ __forceinline__ RawChunk<DT> load_raw(const u32x4* __restrict__ tile, uint32_t tid, uint32_t chunks)
 {
     RawChunk<DT> r;
     if constexpr (DT == kBF16) {
-        r.a = __builtin_nontemporal_load(tile + lane);
+        r.a = __builtin_nontemporal_load(tile + min(tid, chunks - 1u));
     } else {
-        r.a = __builtin_nontemporal_load(tile + 2u * lane);
-        r.b = __builtin_nontemporal_load(tile + 2u * lane + 1u);
+        const uint32_t j = 2u * (tid & ~63u) + (tid & 63u);
+        const uint32_t last = 2u * chunks - 1u;
+        r.a = __builtin_nontemporal_load(tile + min(j, last));
+        r.b = __builtin_nontemporal_load(tile + min(j + 64u, last));
     }
     return r;
 }
 
+// Raw registers -> the lane's 8 consecutive elements as fp32.  fp32 input: the wavefront
+// writes its two 1 KiB load results to its private 2 KiB of LDS and every lane reads back
+// vectors 2l and 2l + 1.  LDS operations of one wavefront execute in program order, so no
+// barrier instruction is needed; the fences keep the compiler from reordering across them.
 template <int DT>
-__device__ __forceinline__ void widen(const RawChunk<DT>& r, float (&v)[8])
+__device__ __forceinline__ void widen(const RawChunk<DT>& r, float (&v)[8], u32x4* wave_lds)
 {
     if constexpr (DT == kBF16) {
         v[0] = u2f(r.a.x << 16); v[1] = u2f(r.a.x & 0xFFFF0000u);
@@ -252,8 +262,15 @@ __device__ __forceinline__ void widen(const RawChunk<DT>& r, float (&v)[8])
         v[4] = u2f(r.a.z << 16); v[5] = u2f(r.a.z & 0xFFFF0000u);
         v[6] = u2f(r.a.w << 16); v[7] = u2f(r.a.w & 0xFFFF0000u);
     } else {
-        v[0] = u2f(r.a.x); v[1] = u2f(r.a.y); v[2] = u2f(r.a.z); v[3] = u2f(r.a.w);
-        v[4] = u2f(r.b.x); v[5] = u2f(r.b.y); v[6] = u2f(r.b.z); v[7] = u2f(r.b.w);
+        const uint32_t l = threadIdx.x & 63u;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        wave_lds[l] = r.a;
+        wave_lds[64u + l] = r.b;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const u32x4 a = wave_lds[2u * l], b = wave_lds[2u * l + 1u];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        v[0] = u2f(a.x); v[1] = u2f(a.y); v[2] = u2f(a.z); v[3] = u2f(a.w);
+        v[4] = u2f(b.x); v[5] = u2f(b.y); v[6] = u2f(b.z); v[7] = u2f(b.w);
     }
 }
 
@@ -320,7 +337,7 @@ __device__ __forceinline__ void load_tile(RawChunk<DT> (&buf)[kItems], const voi
         const uint32_t s = s0 + (uint32_t)i;
         if (s < sl.count) {                                          // uniform
             buf[i] = load_raw<DT>(static_cast<const u32x4*>(x) + (uint64_t)s * kThreads * kVecPerChunk,
-                                  min((uint32_t)threadIdx.x, sl.chunks(s) - 1u));
+                                  (uint32_t)threadIdx.x, sl.chunks(s));
         }
     }
 }
@@ -336,13 +353,13 @@ __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChun
                                             TileOut<B> (&out)[kItems], bool have_prev, uint32_t s_prev,
                                             const void* __restrict__ x, uint32_t s0, uint32_t stride,
                                             Slices sl, float T, float rT, bool pz, const ScaleEntry* tab,
-                                            uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                                            u32x4* wave_lds, uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
                                             float* __restrict__ sse_out)
 {
     float v[kItems][8];
     __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0)
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) widen<DT>(cur[i], v[i]);
+    for (int i = 0; i < kItems; ++i) widen<DT>(cur[i], v[i], wave_lds);
     __builtin_amdgcn_sched_barrier(0);
     if (have_prev) {                                                 // uniform
 #pragma unroll
@@ -364,6 +381,8 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
 {
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
     if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
+    __shared__ u32x4 xpose[(DT == kF32) ? 2 * kThreads : 1];        // 2 KiB per wavefront, fp32 input only
+    u32x4* wave_lds = xpose + ((DT == kF32) ? 2u * (threadIdx.x & ~63u) : 0u);
 
     const Slices sl{n_slices, last_chunks};
     const uint32_t stride = gridDim.x * (uint32_t)kItems;
@@ -380,13 +399,13 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
     uint32_t s_prev = s0;
     while (true) {
         stream_step<DT, B, FMT, FOUR6, TMODE>(bufA, bufB, out, have_prev, s_prev, x, s0, stride, sl,
-                                              T, rT, pz != 0, tab, codes, scales, sse_out);
+                                              T, rT, pz != 0, tab, wave_lds, codes, scales, sse_out);
         have_prev = true;
         s_prev = s0;
         s0 += stride;
         if (s0 >= sl.count) break;
         stream_step<DT, B, FMT, FOUR6, TMODE>(bufB, bufA, out, true, s_prev, x, s0, stride, sl,
-                                              T, rT, pz != 0, tab, codes, scales, sse_out);
+                                              T, rT, pz != 0, tab, wave_lds, codes, scales, sse_out);
         s_prev = s0;
         s0 += stride;
         if (s0 >= sl.count) break;
