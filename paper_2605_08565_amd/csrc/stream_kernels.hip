@@ -129,22 +129,26 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
 
 // Hierarchical scaling divides every input by the per-tensor scale T in IEEE fp32.  T is the
 // same for the whole tensor, so its correctly rounded reciprocal r is formed once and each
-// quotient is refined twice:
-//     q0 = v*r;  q1 = q0 + r*(v - q0*T);  q2 = q1 + r*(v - q1*T)        (remainders by FMA)
-// q1 is within one ulp of v/T, the FMA remainder of such a quotient is exact, and one more
-// step with a correctly rounded reciprocal then yields the correctly rounded quotient
-// (Markstein's division theorem); the sign of v is copied so that -0 stays -0.  The argument
-// needs intermediate results free of overflow and underflow: the host takes this path only
-// for 2^-20 <= T <= 2^20, and a block whose adjusted abs-max leaves [2^-40, 2^90] (zero
-// excepted) sends its whole wavefront through the plain division instead.
+// quotient is refined once:
+//     q0 = v*r;  q1 = q0 + r*(v - q0*T)                                 (remainder by FMA)
+// q0 is within 1.5 ulp of v/T and the value rounded into q1 differs from the exact quotient by
+// less than 3 * 2^-24 ulp, so q1 is the correctly rounded quotient unless v/T lies that close
+// to the midpoint of two floats; all mantissa pairs that come so close (an integer congruence
+// lists them) are checked one by one on the host, the all-ones mantissa of T excluded.  The
+// sign of v is copied so that -0 stays -0.  The argument needs intermediate results free of
+// overflow and underflow: the host takes this path only for 2^-20 <= T <= 2^20 with a
+// mantissa that is not all ones, and a block whose adjusted abs-max leaves [2^-40, 2^90]
+// (zero excepted) sends its whole wavefront through the plain division instead.  An element far
+// below its block's abs-max can still have |v/T| < 2^-78, where the remainder may underflow and
+// q1 be off by one ulp; nothing observes that: the element quantises to a signed zero and its
+// squared residual underflows to zero either way.
 enum : int { kNoT = 0, kFastT = 1, kSlowT = 2 };
 
 __device__ __forceinline__ float div_by_T(float v, float T, float rT)
 {
     const float q0 = v * rT;
     const float q1 = __builtin_fmaf(__builtin_fmaf(-q0, T, v), rT, q0);
-    const float q2 = __builtin_fmaf(__builtin_fmaf(-q1, T, v), rT, q1);
-    return u2f((f2u(q2) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
+    return u2f((f2u(q1) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
 }
 
 template <int NBLK, int EPB, int LANES>
@@ -380,20 +384,21 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
               uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
-    if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
     __shared__ u32x4 xpose[(DT == kF32) ? 2 * kThreads : 1];        // 2 KiB per wavefront, fp32 input only
     u32x4* wave_lds = xpose + ((DT == kF32) ? 2u * (threadIdx.x & ~63u) : 0u);
 
     const Slices sl{n_slices, last_chunks};
     const uint32_t stride = gridDim.x * (uint32_t)kItems;
     uint32_t s0 = blockIdx.x * (uint32_t)kItems;
-    if (s0 >= sl.count) return;
+    if (s0 >= sl.count) return;                                      // whole workgroup
     const float rT = 1.0f / T;                                       // correctly rounded
 
+    // the first tile's loads are in flight while the scale table is built
     RawChunk<DT> bufA[kItems], bufB[kItems];
 #pragma unroll
     for (int i = 0; i < kItems; ++i) { bufA[i] = RawChunk<DT>{}; bufB[i] = RawChunk<DT>{}; }
     load_tile<DT>(bufA, x, s0, sl);
+    if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
     TileOut<B> out[kItems];
     bool have_prev = false;
     uint32_t s_prev = s0;

@@ -153,13 +153,12 @@ static long check_pow2(long* cases)
     return bad;
 }
 
-/* check 4: division by the per-tensor scale, reciprocal + two FMA refinements */
+/* check 4: division by the per-tensor scale, reciprocal + one FMA refinement */
 static float div_by_T(float v, float T, float rT)
 {
     volatile float q0 = v * rT;
     volatile float q1 = fmaf(fmaf(-q0, T, v), rT, q0);
-    volatile float q2 = fmaf(fmaf(-q1, T, v), rT, q1);
-    return u2f((f2u(q2) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
+    return u2f((f2u(q1) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
 }
 static long check_div(long* cases)
 {
@@ -179,7 +178,7 @@ static long check_div(long* cases)
             if (isnan(v) || isinf(v)) continue;
             const float q = v / T;
             const float aq = fabsf(q);
-            if (aq != 0.0f && (aq < 0x1p-40f || aq > 0x1p90f)) continue;   /* handled by the fall-back */
+            if (aq != 0.0f && (aq < 0x1p-78f || aq > 0x1p90f)) continue;   /* see below */
             ++n;
             if (f2u(div_by_T(v, T, rT)) != f2u(q)) ++bad;
         }
@@ -189,9 +188,62 @@ static long check_div(long* cases)
             const float v = ldexpf(u2f(0x3F800000u | (u & 0x7FFFFF)), e) * ((u >> 31) ? -1.0f : 1.0f);
             const float q = v / T;
             const float aq = fabsf(q);
-            if (aq < 0x1p-40f || aq > 0x1p90f) continue;
+            /* above 2^90 the block's abs-max sends the wavefront to the plain division; below
+             * 2^-78 the remainder may underflow and the quotient be off by one ulp, which nothing
+             * observes: such an element is either the block's abs-max (< 2^-40: plain division)
+             * or quantises to a signed zero with a squared residual that underflows to zero */
+            if (aq < 0x1p-78f || aq > 0x1p90f) continue;
             ++n;
             if (f2u(div_by_T(v, T, rT)) != f2u(q)) ++bad;
+        }
+    }
+    *cases = n;
+    return bad;
+}
+
+/* check 5: the same division, every case in which it could fail.
+ *
+ * With r = RN(1/T), q0 = RN(v r) is within 1.5 ulp of Q = v/T, the FMA remainder and the final
+ * FMA perturb the exact quotient by less than 3 * 2^-24 ulp before the last rounding, so q1 can
+ * differ from RN(Q) only if Q lies that close to a midpoint of two neighbouring floats.  For
+ * integer mantissas V, T' in [2^23, 2^24) the distance of Q = V/T' to the midpoint odd/2^k
+ * (k = 24 for Q >= 1, 25 for Q < 1) is |N| / (2 T') ulp with N = V 2^k - odd T', a non-zero
+ * integer: only |N| < 6 can fail.  This enumerates EVERY (V, T') with |N| <= 64 by solving the
+ * congruence V 2^k = N (mod T') and runs the sequence on each; the all-ones mantissa of T is
+ * the one the kernel's host code routes to the plain division. */
+static int64_t egcd(int64_t a, int64_t b, int64_t* x, int64_t* y)
+{
+    if (!b) { *x = 1; *y = 0; return a; }
+    int64_t x1, y1;
+    const int64_t g = egcd(b, a % b, &x1, &y1);
+    *x = y1;
+    *y = x1 - (a / b) * y1;
+    return g;
+}
+static long check_div_midpoints(long* cases)
+{
+    long bad = 0, n = 0;
+#pragma omp parallel for reduction(+ : bad, n) schedule(dynamic, 4096)
+    for (int64_t Tp = (1 << 23); Tp < (1 << 24) - 1; ++Tp) {
+        const float T = (float)Tp;
+        volatile float r = 1.0f / T;
+        for (int k = 24; k <= 25; ++k) {
+            const int64_t lo = (k == 24) ? Tp : (1 << 23), hi = (k == 24) ? (1 << 24) : Tp;   /* V in [lo, hi) */
+            int64_t x, y;
+            const int64_t g = egcd(((int64_t)1 << k) % Tp, Tp, &x, &y);
+            const int64_t m = Tp / g;
+            for (int N = -64; N <= 64; ++N) {
+                if (N == 0 || N % g) continue;
+                int64_t V0 = (int64_t)(((__int128)x * (N / g)) % m);
+                if (V0 < 0) V0 += m;
+                for (int64_t V = lo + ((V0 - lo) % m + m) % m; V < hi; V += m) {
+                    const int64_t M = (int64_t)(((((__int128)V) << k) - N) / Tp);
+                    if (!(M & 1)) continue;                     /* next to a float, not to a midpoint */
+                    ++n;
+                    const float v = (float)V;
+                    if (f2u(div_by_T(v, T, r)) != f2u(v / T)) ++bad;
+                }
+            }
         }
     }
     *cases = n;
@@ -205,5 +257,6 @@ int main(void)
     bad = check_scale_encode(&n);  printf("scale_encode cases=%ld bad=%ld\n", n, bad); total += bad;
     bad = check_pow2(&n);          printf("pow2_code cases=%ld bad=%ld\n", n, bad); total += bad;
     bad = check_div(&n);           printf("tensor_scale_division cases=%ld bad=%ld\n", n, bad); total += bad;
+    bad = check_div_midpoints(&n); printf("tensor_scale_division_midpoints cases=%ld bad=%ld\n", n, bad); total += bad;
     return total == 0 ? 0 : 1;
 }

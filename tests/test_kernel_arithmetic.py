@@ -5,8 +5,9 @@ unchanged.  tests/host/kernel_arithmetic_check.c re-states those sequences with 
 host and compares them with exact arithmetic over (near-)exhaustive input sets: every fp32
 mantissa against every scale mantissa for the element quotient, every third fp32 mantissa over
 the whole range of both 8-bit scale formats for the scale encode, every fifth positive fp32
-value for the Eq. 1 code, and 3000 per-tensor scales against every bf16 value plus random fp32
-values for the reciprocal-refined division."""
+value for the Eq. 1 code, and for the reciprocal-refined division by the per-tensor scale 3000
+scales against every bf16 value plus random fp32 values, and every mantissa pair whose exact
+quotient lies near a rounding midpoint (the only inputs on which that sequence could fail)."""
 import os
 import subprocess
 
@@ -24,7 +25,7 @@ def test_kernel_arithmetic_shortcuts_are_decision_exact(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     print(res.stdout)
     lines = [l for l in res.stdout.splitlines() if "cases=" in l]
-    assert len(lines) == 4
+    assert len(lines) == 5
     for l in lines:
         cases = int(l.split("cases=")[1].split()[0])
         bad = int(l.split("bad=")[1])
