@@ -7,7 +7,8 @@ every block size, one layer resident on the GPU at a time.
 Recipes: power-of-two MX (E8M0 abs-max), E4M3 abs-max, E4M3 prevent-zero, E4M3 4-over-6,
 UE5M3 abs-max, E4M3 brute force; block sizes 2 ... 128.  For every (recipe, block size) the
 seven matrices of a layer are quantised back to back (436 MB of input between two touches of
-a matrix, so the 256 MB Infinity Cache does not help) with one event pair around the group.
+a matrix, so the 256 MB Infinity Cache does not help), as one HIP graph replay with one event
+pair around it.
 Reports GElem/s and the aggregate MSE per (recipe, block size).  Weights are drawn on the GPU
 (this driver measures throughput and quality trends; bit-parity with the CPU oracle is the
 job of the tests, which use the numpy generator of ``workloads``).
@@ -25,49 +26,73 @@ RECIPES = [("pow2_mx", 0, 0), ("e4m3_absmax", 1, 0), ("e4m3_prevent_zero", 1, 1)
 BLOCKS = (2, 4, 8, 16, 32, 64, 128)
 
 
-def layer_on_gpu(layer: int, dev):
-    """The seven weight matrices of one layer, drawn on the GPU: 0.02 * Z / sqrt(chi2_4 / 4)."""
+def draw_layer(layer: int, mats) -> None:
+    """Fill the seven resident weight buffers with layer `layer`, drawn on the GPU:
+    0.02 * Z / sqrt(chi2_4 / 4)."""
     import torch
-    mats = {}
-    for idx, (name, (r, c)) in enumerate(LAYER_SHAPES.items()):
-        g = torch.Generator(device=dev)
+    for idx, (name, x) in enumerate(mats.items()):
+        g = torch.Generator(device=x.device)
         g.manual_seed(50_000 + 16 * layer + idx)
-        z = torch.randn((r, c), generator=g, device=dev, dtype=torch.float32)
-        chi = torch.zeros((r, c), device=dev, dtype=torch.float32)
+        z = torch.randn(x.shape, generator=g, device=x.device, dtype=torch.float32)
+        chi = torch.zeros(x.shape, device=x.device, dtype=torch.float32)
         for _ in range(4):
-            chi += torch.randn((r, c), generator=g, device=dev, dtype=torch.float32) ** 2
-        mats[name] = (0.02 * z / torch.sqrt(chi / 4.0)).to(torch.bfloat16).contiguous()
-    return mats
+            chi += torch.randn(x.shape, generator=g, device=x.device, dtype=torch.float32) ** 2
+        x.copy_(0.02 * z / torch.sqrt(chi / 4.0))
 
 
-def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES) -> dict:
+def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool = True) -> dict:
+    """The smallest matrices (k, v: 4 M elements) quantise in a few microseconds, less than one
+    launch through Python costs, so the seven launches of a (recipe, block size) group are
+    captured once into a HIP graph over resident buffers and replayed for every layer."""
     import torch
 
     from . import mxq
 
     dev = torch.device("cuda:0")
-    n_max = max(r * c for r, c in LAYER_SHAPES.values())
+    mats = {name: torch.empty((r, c), dtype=torch.bfloat16, device=dev) for name, (r, c) in LAYER_SHAPES.items()}
     outs = {name: (torch.empty(r * c // 2, dtype=torch.uint8, device=dev),
                    torch.empty(r * c // 2, dtype=torch.uint8, device=dev),
                    torch.empty(r * c // 2, dtype=torch.float32, device=dev))
             for name, (r, c) in LAYER_SHAPES.items()}
-    del n_max
+
+    def group(b, fmt, rec):
+        for name, x in mats.items():
+            r, c = x.shape
+            co, so, eo = outs[name]
+            nb = r * c // b
+            mxq.quantize(x, b, fmt, rec, codes_out=co.view(r, c // 2),
+                         scales_out=so[:nb].view(r, c // b), sse_out=eo[:nb].view(r, c // b))
+
     acc = {(rn, b): {"ms": 0.0, "elements": 0, "sse": 0.0} for rn, _, _ in recipes for b in blocks}
+    warm = torch.zeros((8, 256), dtype=torch.bfloat16, device=dev)
+    for _, fmt, rec in recipes:                      # untimed: the runtime loads each kernel on first use
+        for b in blocks:
+            mxq.quantize(warm, b, fmt, rec)
+    torch.cuda.synchronize()
+    graphs = {}
+    if use_graphs:
+        for m in mats.values():
+            m.zero_()
+        side = torch.cuda.Stream()
+        for rn, fmt, rec in recipes:
+            for b in blocks:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    group(b, fmt, rec)
+                graphs[(rn, b)] = g
+        torch.cuda.synchronize()
+
     for layer in range(layers):
-        mats = layer_on_gpu(layer, dev)
-        for x in mats.values():                      # untimed first touch of the new tensors
-            mxq.tensor_absmax(x)
+        draw_layer(layer, mats)
         torch.cuda.synchronize()
         for rn, fmt, rec in recipes:
             for b in blocks:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                for name, x in mats.items():
-                    r, c = x.shape
-                    co, so, eo = outs[name]
-                    nb = r * c // b
-                    mxq.quantize(x, b, fmt, rec, codes_out=co.view(r, c // 2),
-                                 scales_out=so[:nb].view(r, c // b), sse_out=eo[:nb].view(r, c // b))
+                if use_graphs:
+                    graphs[(rn, b)].replay()
+                else:
+                    group(b, fmt, rec)
                 e1.record()
                 torch.cuda.synchronize()
                 a = acc[(rn, b)]
@@ -75,20 +100,20 @@ def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES) -> dict:
                 for name, x in mats.items():
                     a["elements"] += x.numel()
                     a["sse"] += float(outs[name][2][: x.numel() // b].to(torch.float64).sum())
-        del mats
     rows = []
     for (rn, b), a in acc.items():
         rows.append({"recipe": rn, "block": b, "gelem_s": round(a["elements"] / a["ms"] / 1e6, 1),
                      "mse": a["sse"] / a["elements"], "elements": a["elements"], "ms": round(a["ms"], 3)})
-    return {"layers": layers, "rows": rows}
+    return {"layers": layers, "graphs": use_graphs, "rows": rows}
 
 
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=N_LAYERS)
     ap.add_argument("--out", default="")
+    ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from Python instead")
     args = ap.parse_args()
-    res = run(args.layers)
+    res = run(args.layers, use_graphs=not args.no_graphs)
     text = json.dumps(res)
     if args.out:
         with open(args.out, "w") as f:

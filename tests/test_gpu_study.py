@@ -66,3 +66,6 @@ def test_model_sweep_driver_one_layer():
         assert mse[("pow2_mx", b)] > mse[("e4m3_absmax", b)]
     assert mse[("e4m3_brute", 4)] < mse[("e4m3_brute", 16)] < mse[("e4m3_brute", 64)]
     assert all(r["gelem_s"] > 1 for r in res["rows"])
+    # the graph replays compute what plain launches compute
+    plain = sweep.run(layers=1, blocks=(4, 16, 64), use_graphs=False)
+    assert {(r["recipe"], r["block"]): r["mse"] for r in plain["rows"]} == mse
