@@ -130,12 +130,14 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
 // Hierarchical scaling divides every input by the per-tensor scale T in IEEE fp32.  T is the
 // same for the whole tensor, so its correctly rounded reciprocal r is formed once and each
 // quotient is refined once:
-//     q0 = v*r;  q1 = q0 + r*(v - q0*T)                                 (remainder by FMA)
+//     q0 = v*r;  q1 = q0 - r*(q0*T - v)                                 (remainder by FMA)
 // q0 is within 1.5 ulp of v/T and the value rounded into q1 differs from the exact quotient by
 // less than 3 * 2^-24 ulp, so q1 is the correctly rounded quotient unless v/T lies that close
 // to the midpoint of two floats; all mantissa pairs that come so close (an integer congruence
 // lists them) are checked one by one on the host, the all-ones mantissa of T excluded.  The
-// sign of v is copied so that -0 stays -0.  The argument needs intermediate results free of
+// remainder is formed with the opposite sign (q0*T - v) and subtracted, which keeps a signed
+// zero: for v = -0 the last step is (-0)*r + (-0) = -0, whereas v - q0*T would give +0 and
+// lose the sign.  The argument needs intermediate results free of
 // overflow and underflow: the host takes this path only for 2^-20 <= T <= 2^20 with a
 // mantissa that is not all ones, and a block whose adjusted abs-max leaves [2^-40, 2^90]
 // (zero excepted) sends its whole wavefront through the plain division instead.  An element far
@@ -147,8 +149,8 @@ enum : int { kNoT = 0, kFastT = 1, kSlowT = 2 };
 __device__ __forceinline__ float div_by_T(float v, float T, float rT)
 {
     const float q0 = v * rT;
-    const float q1 = __builtin_fmaf(__builtin_fmaf(-q0, T, v), rT, q0);
-    return u2f((f2u(q1) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
+    const float neg_rem = __builtin_fmaf(q0, T, -v);                 // q0*T - v, exact
+    return __builtin_fmaf(-neg_rem, rT, q0);
 }
 
 template <int NBLK, int EPB, int LANES>

@@ -153,12 +153,13 @@ static long check_pow2(long* cases)
     return bad;
 }
 
-/* check 4: division by the per-tensor scale, reciprocal + one FMA refinement */
+/* check 4: division by the per-tensor scale, reciprocal + one FMA refinement; the remainder is
+ * taken with the opposite sign so that signed zeros survive (every bf16 value includes -0) */
 static float div_by_T(float v, float T, float rT)
 {
     volatile float q0 = v * rT;
-    volatile float q1 = fmaf(fmaf(-q0, T, v), rT, q0);
-    return u2f((f2u(q1) & 0x7FFFFFFFu) | (f2u(v) & 0x80000000u));
+    volatile float neg_rem = fmaf(q0, T, -v);
+    return fmaf(-neg_rem, rT, q0);
 }
 static long check_div(long* cases)
 {
