@@ -83,6 +83,20 @@ def _check(status: int) -> None:
         raise MxqError(status)
 
 
+def _need(t: torch.Tensor, nbytes: int, name: str, dtype: torch.dtype | None = None) -> None:
+    """The library trusts its pointers: refuse a buffer it would read or write past."""
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous tensor on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}")
+    if t.numel() * t.element_size() < nbytes:
+        raise ValueError(f"{name} holds {t.numel() * t.element_size()} bytes, {nbytes} are needed")
+
+
+def _nblocks(rows: int, cols: int, block: int) -> int:
+    return rows * (cols // block) if block > 0 else 0
+
+
 def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_scale: float = 1.0,
              codes_out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None,
              sse_out: torch.Tensor | None = None, want_sse: bool = True, stream=None,
@@ -98,6 +112,10 @@ def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_sc
         scales_out = torch.empty((rows, cols // block if block > 0 else 0), dtype=torch.uint8, device=dev)
     if sse_out is None and want_sse:
         sse_out = torch.empty((rows, cols // block if block > 0 else 0), dtype=torch.float32, device=dev)
+    _need(codes_out, rows * cols // 2, "codes_out", torch.uint8)
+    _need(scales_out, _nblocks(rows, cols, block), "scales_out", torch.uint8)
+    if sse_out is not None:
+        _need(sse_out, 4 * _nblocks(rows, cols, block), "sse_out", torch.float32)
     _check(lib().mxq_quantize(x.data_ptr(), rows, cols, block, elem_fmt, scale_fmt, recipe,
                               float(tensor_scale), codes_out.data_ptr(), scales_out.data_ptr(),
                               sse_out.data_ptr() if sse_out is not None else None,
@@ -112,6 +130,9 @@ def dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt:
     cols = half * 2
     if out is None:
         out = torch.empty((rows, cols), dtype=out_dtype, device=codes.device)
+    _need(codes, rows * half, "codes", torch.uint8)
+    _need(scales, _nblocks(rows, cols, block), "scales", torch.uint8)
+    _need(out, rows * cols * out.element_size(), "out")
     _check(lib().mxq_dequantize(codes.data_ptr(), scales.data_ptr(), rows, cols, block, elem_fmt,
                                 scale_fmt, float(tensor_scale), out.data_ptr(), _dtype_code(out),
                                 _stream_ptr(stream)))
@@ -124,6 +145,7 @@ def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None)
         raise ValueError("x must be a contiguous tensor on the GPU")
     if out is None:
         out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _need(out, 4, "out", torch.float32)
     rows = x.shape[0] if x.dim() == 2 else 1
     cols = x.shape[1] if x.dim() == 2 else x.numel()
     _check(lib().mxq_tensor_absmax(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
@@ -135,9 +157,13 @@ def clip_sse(x: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt: int,
              tensor_scale: float = 1.0, out: torch.Tensor | None = None, stream=None,
              elem_fmt: int = ELEM_E2M1) -> torch.Tensor:
     """mxq_clip_sse: clipping-only part of the block SSE for the given scale bytes."""
+    if not x.is_cuda or x.dim() != 2 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
     rows, cols = x.shape
     if out is None:
         out = torch.empty((rows, cols // block), dtype=torch.float32, device=x.device)
+    _need(scales, _nblocks(rows, cols, block), "scales", torch.uint8)
+    _need(out, 4 * _nblocks(rows, cols, block), "out", torch.float32)
     _check(lib().mxq_clip_sse(x.data_ptr(), scales.data_ptr(), rows, cols, block, elem_fmt, scale_fmt,
                               float(tensor_scale), out.data_ptr(), _dtype_code(x), _stream_ptr(stream)))
     return out
@@ -147,6 +173,8 @@ def histogram(codes: torch.Tensor, scales: torch.Tensor, block: int, stream=None
               elem_fmt: int = ELEM_E2M1):
     """mxq_histogram: (int64 [8] magnitude-index counts, int64 [256] scale-byte counts)."""
     rows, half = codes.shape
+    _need(codes, rows * half, "codes", torch.uint8)
+    _need(scales, _nblocks(rows, half * 2, block), "scales", torch.uint8)
     eh = torch.empty(8, dtype=torch.int64, device=codes.device)
     sh = torch.empty(256, dtype=torch.int64, device=codes.device)
     _check(lib().mxq_histogram(codes.data_ptr(), scales.data_ptr(), rows, half * 2, block, elem_fmt,

@@ -128,6 +128,32 @@ def test_ragged_and_tiny_shapes(oracle, mxq):
                 check(oracle, mxq, x, block, fmt, rec, tag="ragged")
 
 
+def test_binding_refuses_buffers_that_are_too_small(mxq):
+    """The library trusts its pointers, so the binding checks every caller-supplied buffer."""
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    u8 = lambda n: torch.empty(n, dtype=torch.uint8, device="cuda")
+    f32 = lambda n: torch.empty(n, dtype=torch.float32, device="cuda")
+    with pytest.raises(ValueError):
+        mxq.quantize(x, 16, 1, 0, codes_out=u8(127))
+    with pytest.raises(ValueError):
+        mxq.quantize(x, 16, 1, 0, scales_out=u8(15))
+    with pytest.raises(ValueError):
+        mxq.quantize(x, 16, 1, 0, sse_out=f32(15))
+    with pytest.raises(TypeError):
+        mxq.quantize(x, 16, 1, 0, sse_out=u8(64))
+    c, s_, _ = mxq.quantize(x, 16, 1, 0)
+    with pytest.raises(ValueError):
+        mxq.dequantize(c, s_[:3], 16, 1)
+    with pytest.raises(ValueError):
+        mxq.dequantize(c, s_, 16, 1, out=f32(255))
+    with pytest.raises(ValueError):
+        mxq.clip_sse(x, s_[:3], 16, 1)
+    with pytest.raises(ValueError):
+        mxq.histogram(c, s_[:3], 16)
+    with pytest.raises(ValueError):
+        mxq.quantize(x.cpu(), 16, 1, 0)
+
+
 def test_empty(mxq):
     x = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     c, s, e = mxq.quantize(x, 16, 1, 0)
