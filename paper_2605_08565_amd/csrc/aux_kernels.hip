@@ -153,17 +153,21 @@ hipError_t launch_dequant(const DequantArgs& a)
 // captured in a graph).
 __global__ void absmax_clear_kernel(uint32_t* out) { *out = 0u; }
 
-// Each workgroup walks tiles of 4 x 256 chunks with four independent 128-bit loads per lane in
-// flight; the ragged last chunk (n not a multiple of 8) is read element-wise by one lane.
+// One workgroup of 1024 threads per compute unit walks tiles of 4 x 1024 vectors with four
+// independent 128-bit loads per lane in flight (16 MiB over the chip); the ragged last chunk (n
+// not a multiple of 8) is read element-wise by one lane.  Few, large workgroups because the
+// closing accesses to the one output word serialise at about 5 ns each, whatever their kind.
 constexpr int kAbsItems = 4;
+constexpr int kAbsThreads = 1024;
+constexpr int kAbsMaxGrid = 256;
 
 template <int DT>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kAbsThreads)
 absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out)
 {
     constexpr int64_t kVec = (DT == kBF16) ? 1 : 2;               // 128-bit vectors per chunk
     const int64_t n_vec = (n >> 3) * kVec;                         // complete vectors
-    const int64_t tile = (int64_t)kThreads * kAbsItems;
+    const int64_t tile = (int64_t)kAbsThreads * kAbsItems;
     const int64_t stride = (int64_t)gridDim.x * tile;
     const u32x4* xv = static_cast<const u32x4*>(x);
     uint32_t m = 0u;
@@ -171,10 +175,10 @@ absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out)
         u32x4 r[kAbsItems];
 #pragma unroll
         for (int i = 0; i < kAbsItems; ++i) {
-            const int64_t vi = v0 + (int64_t)i * kThreads;
+            const int64_t vi = v0 + (int64_t)i * kAbsThreads;
             r[i] = u32x4{0u, 0u, 0u, 0u};
             if (vi < n_vec) {                                                               // uniform
-                const uint32_t left = (uint32_t)min((int64_t)kThreads, n_vec - vi);
+                const uint32_t left = (uint32_t)min((int64_t)kAbsThreads, n_vec - vi);
                 r[i] = __builtin_nontemporal_load(xv + vi + min((uint32_t)threadIdx.x, left - 1u));
             }
         }
@@ -203,13 +207,16 @@ absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out)
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
-    __shared__ uint32_t part[kThreads / 64];
+    __shared__ uint32_t part[kAbsThreads / 64];
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t w = part[0];
-        for (int i = 1; i < kThreads / 64; ++i) w = max(w, part[i]);
-        atomicMax(out, w);
+        for (int i = 1; i < kAbsThreads / 64; ++i) w = max(w, part[i]);
+        // The word only grows, so a workgroup whose maximum does not exceed the value it reads
+        // (at device scope, past the per-CU cache) has nothing to add: after the first few
+        // workgroups almost none issues the atomic, which would otherwise serialise on one word.
+        if (w > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out, w);
     }
 }
 
@@ -218,15 +225,13 @@ hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, hipStr
     hipLaunchKernelGGL(absmax_clear_kernel, dim3(1), dim3(1), 0, stream, (uint32_t*)out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
-    // one workgroup per 1024 chunks, at most two workgroups per compute unit: few enough that
-    // the closing atomic max (one per workgroup, all on one word) stays cheap
-    const int64_t n_tiles = ((n + 7) / 8 + kThreads * kAbsItems - 1) / (kThreads * kAbsItems);
-    const int64_t capw = 512;
+    const int64_t n_tiles = ((n + 7) / 8 + kAbsThreads * kAbsItems - 1) / (kAbsThreads * kAbsItems);
+    const int64_t capw = kAbsMaxGrid;
     const int grid = (int)(n_tiles < 1 ? 1 : (n_tiles < capw ? n_tiles : capw));
     if (dtype == kBF16)
-        hipLaunchKernelGGL((absmax_kernel<kBF16>), dim3(grid), dim3(kThreads), 0, stream, x, n, (uint32_t*)out);
+        hipLaunchKernelGGL((absmax_kernel<kBF16>), dim3(grid), dim3(kAbsThreads), 0, stream, x, n, (uint32_t*)out);
     else
-        hipLaunchKernelGGL((absmax_kernel<kF32>), dim3(grid), dim3(kThreads), 0, stream, x, n, (uint32_t*)out);
+        hipLaunchKernelGGL((absmax_kernel<kF32>), dim3(grid), dim3(kAbsThreads), 0, stream, x, n, (uint32_t*)out);
     return hipGetLastError();
 }
 
