@@ -88,10 +88,22 @@ hipError_t launch_clip_sse(const void* x, const uint8_t* scales, int64_t n, int 
     return hipGetLastError();
 }
 
-// Histograms.  Element magnitudes are counted per lane in registers over the whole grid-stride
-// loop (nibble-parallel compares on the packed dword), scale bytes go through a per-workgroup
-// LDS histogram; both meet in 64-bit atomics on the caller's arrays, which a small kernel
-// clears first.
+// Histograms.  Both arrays are read with 128-bit loads.
+//
+// Element magnitudes: the low three bits of the 32 nibbles in a 128-bit vector are transposed
+// into three 32-bit planes (plane p holds bit p of every nibble: the four dwords' bit-p masks
+// 0x11111111 << p are shifted to interleave), and each of the 8 magnitudes is one boolean
+// function of the three planes followed by a population count that adds into a per-lane
+// register counter: about 40 vector instructions per 32 elements.
+//
+// Scale bytes: a per-workgroup LDS histogram with one copy per lane of a wavefront (64 copies,
+// word [code][lane]: 64 KiB), so that the lanes of one LDS atomic never meet on a word, however
+// popular a code is, and fall on the banks like any 64-lane access.
+//
+// Partial results meet in 64-bit atomics on the caller's arrays, which a small kernel clears
+// first; few, large workgroups keep the number of those atomics small.  The bytes before the
+// first 16-byte boundary, those after the last complete vector and a ragged last dword are
+// counted serially by one thread.
 __global__ void hist_clear_kernel(unsigned long long* elem_hist, unsigned long long* scale_hist)
 {
     const uint32_t t = threadIdx.x;
@@ -99,51 +111,112 @@ __global__ void hist_clear_kernel(unsigned long long* elem_hist, unsigned long l
     scale_hist[t] = 0ull;
 }
 
-// number of nibbles of w whose low three bits equal k
-__device__ __forceinline__ uint32_t count_mag(uint32_t w, uint32_t k)
+constexpr int kHistThreads = 1024;
+constexpr int kHistCopies = 64;
+constexpr int kHistMaxGrid = 256;
+static_assert(kHistThreads == 4 * 256 && kHistCopies == 64, "the closing reduction maps four threads to a code");
+
+// cnt[k] += number of nibbles of the four dwords whose low three bits equal k
+__device__ __forceinline__ void count_magnitudes(const u32x4 w, uint32_t (&cnt)[8])
 {
-    const uint32_t d = (w ^ (k * 0x11111111u)) & 0x77777777u;          // zero nibble <=> match
-    const uint32_t nz = (d | (d >> 1) | (d >> 2)) & 0x11111111u;       // 1 per non-matching nibble
-    return 8u - (uint32_t)__builtin_popcount(nz);
+    constexpr uint32_t M0 = 0x11111111u, M1 = 0x22222222u, M2 = 0x44444444u;
+    const uint32_t p0 = (w.x & M0) | ((w.y & M0) << 1) | ((w.z & M0) << 2) | ((w.w & M0) << 3);
+    const uint32_t p1 = ((w.x & M1) >> 1) | (w.y & M1) | ((w.z & M1) << 1) | ((w.w & M1) << 2);
+    const uint32_t p2 = ((w.x & M2) >> 2) | ((w.y & M2) >> 1) | (w.z & M2) | ((w.w & M2) << 1);
+    cnt[0] += (uint32_t)__builtin_popcount(~p2 & ~p1 & ~p0);
+    cnt[1] += (uint32_t)__builtin_popcount(~p2 & ~p1 & p0);
+    cnt[2] += (uint32_t)__builtin_popcount(~p2 & p1 & ~p0);
+    cnt[3] += (uint32_t)__builtin_popcount(~p2 & p1 & p0);
+    cnt[4] += (uint32_t)__builtin_popcount(p2 & ~p1 & ~p0);
+    cnt[5] += (uint32_t)__builtin_popcount(p2 & ~p1 & p0);
+    cnt[6] += (uint32_t)__builtin_popcount(p2 & p1 & ~p0);
+    cnt[7] += (uint32_t)__builtin_popcount(p2 & p1 & p0);
 }
 
-static_assert(kThreads == 256, "the scale histogram uses one LDS counter per thread");
-
-__global__ void __launch_bounds__(kThreads)
-histogram_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
+__global__ void __launch_bounds__(kHistThreads)
+histogram_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
                  int64_t n_blocks, unsigned long long* __restrict__ elem_hist,
                  unsigned long long* __restrict__ scale_hist)
 {
-    __shared__ uint32_t sh_scale[256];
+    __shared__ uint32_t sh_scale[kHistCopies * 256];
     __shared__ uint32_t sh_elem[8];
-    sh_scale[threadIdx.x] = 0u;
+    for (uint32_t i = threadIdx.x; i < (uint32_t)(kHistCopies * 256); i += kHistThreads) sh_scale[i] = 0u;
     if (threadIdx.x < 8) sh_elem[threadIdx.x] = 0u;
     __syncthreads();
 
+    const int64_t stride = (int64_t)gridDim.x * kHistThreads;
+    const int64_t t0 = (int64_t)blockIdx.x * kHistThreads + threadIdx.x;
+
+    // packed codes: n / 2 bytes = head bytes, n_vec aligned 16-byte vectors, tail bytes
+    const int64_t code_bytes = n >> 1;
+    const int64_t c_head = min(code_bytes, (int64_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(codes) & 15u)) & 15u));
+    const int64_t c_vec = (code_bytes - c_head) >> 4;
+    const u32x4* cv = reinterpret_cast<const u32x4*>(codes + c_head);
     uint32_t cnt[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    const int64_t n_dwords = n >> 3;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    for (int64_t i = t0; i < n_dwords; i += stride) {
-        const uint32_t w = __builtin_nontemporal_load(codes + i);
+    for (int64_t i = t0; i < c_vec; i += 4 * stride) {               // four loads in flight per lane
+        u32x4 r[4];
 #pragma unroll
-        for (uint32_t k = 0; k < 8u; ++k) cnt[k] += count_mag(w, k);
+        for (int u = 0; u < 4; ++u) r[u] = __builtin_nontemporal_load(cv + min(i + u * stride, c_vec - 1));
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * stride < c_vec) count_magnitudes(r[u], cnt);
     }
-    if (t0 == 0) {                                                   // ragged tail: < 8 elements
-        const uint8_t* cb = reinterpret_cast<const uint8_t*>(codes);
-        for (int64_t e = n_dwords << 3; e < n; ++e) cnt[(cb[e >> 1] >> ((e & 1) * 4)) & 7u] += 1u;
+
+    // scale bytes: the same split
+    const int64_t s_head = min(n_blocks, (int64_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(scales) & 15u)) & 15u));
+    const int64_t s_vec = (n_blocks - s_head) >> 4;
+    const u32x4* sv = reinterpret_cast<const u32x4*>(scales + s_head);
+    uint32_t* mine = sh_scale + (threadIdx.x & (kHistCopies - 1));        // word of code c: mine[c * 64]
+    for (int64_t i = t0; i < s_vec; i += 2 * stride) {               // two loads in flight per lane
+        u32x4 r[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) r[u] = __builtin_nontemporal_load(sv + min(i + u * stride, s_vec - 1));
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (i + u * stride >= s_vec) continue;
+            const uint32_t d[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                atomicAdd(&mine[(d[j] & 0xFFu) * kHistCopies], 1u);
+                atomicAdd(&mine[((d[j] >> 8) & 0xFFu) * kHistCopies], 1u);
+                atomicAdd(&mine[((d[j] >> 16) & 0xFFu) * kHistCopies], 1u);
+                atomicAdd(&mine[(d[j] >> 24) * kHistCopies], 1u);
+            }
+        }
     }
-    for (int64_t b = t0; b < n_blocks; b += stride) atomicAdd(&sh_scale[scales[b]], 1u);
+
+    if (t0 == 0) {                                                   // the few bytes outside the vectors
+        for (int64_t b = 0; b < code_bytes; ++b) {
+            if (b == c_head) b += c_vec << 4;
+            if (b >= code_bytes) break;
+            cnt[codes[b] & 7u] += 1u;
+            cnt[(codes[b] >> 4) & 7u] += 1u;
+        }
+        for (int64_t b = 0; b < n_blocks; ++b) {
+            if (b == s_head) b += s_vec << 4;
+            if (b >= n_blocks) break;
+            atomicAdd(&mine[(uint32_t)scales[b] * kHistCopies], 1u);
+        }
+    }
+
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         uint32_t c = cnt[k];
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) c += (uint32_t)__shfl_xor((int)c, off, 64);
-        if ((threadIdx.x & 63) == 0) atomicAdd(&sh_elem[k], c);
+        if ((threadIdx.x & 63) == 0 && c) atomicAdd(&sh_elem[k], c);
     }
     __syncthreads();
     if (threadIdx.x < 8 && sh_elem[threadIdx.x]) atomicAdd(&elem_hist[threadIdx.x], (unsigned long long)sh_elem[threadIdx.x]);
-    if (sh_scale[threadIdx.x]) atomicAdd(&scale_hist[threadIdx.x], (unsigned long long)sh_scale[threadIdx.x]);
+    {   // four threads per code, 16 copies each
+        const uint32_t code = threadIdx.x >> 2, part = threadIdx.x & 3u;
+        uint32_t c = 0u;
+#pragma unroll
+        for (int r = 0; r < kHistCopies / 4; ++r) c += sh_scale[code * kHistCopies + part * (kHistCopies / 4) + r];
+        c += (uint32_t)__shfl_xor((int)c, 1, 64);
+        c += (uint32_t)__shfl_xor((int)c, 2, 64);
+        if (part == 0u && c) atomicAdd(&scale_hist[code], (unsigned long long)c);
+    }
 }
 
 hipError_t launch_histogram(const uint8_t* codes, const uint8_t* scales, int64_t n, int block,
@@ -153,15 +226,15 @@ hipError_t launch_histogram(const uint8_t* codes, const uint8_t* scales, int64_t
     hipLaunchKernelGGL(hist_clear_kernel, dim3(1), dim3(256), 0, stream, elem_hist, scale_hist);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
-    // a lane's register counters are 32-bit and a workgroup's LDS counters too: bound the work
-    // per workgroup to < 2^32 elements by using enough workgroups (one per 2^21 dwords at least)
-    const int64_t n_dwords = (n + 7) / 8;
-    int64_t grid = (n_dwords + kThreads * 16 - 1) / (kThreads * 16);
-    if (grid > 1024) grid = 1024;
-    const int64_t min_grid = (n_dwords >> 21) + 1;
+    // a lane's register counters and a workgroup's LDS counters are 32-bit: keep the elements
+    // per workgroup below 2^32 by using enough workgroups (at least one per 2^31 elements)
+    const int64_t n_vec = (n + 31) / 32;
+    int64_t grid = (n_vec + kHistThreads - 1) / kHistThreads;
+    if (grid > kHistMaxGrid) grid = kHistMaxGrid;
+    const int64_t min_grid = (n >> 31) + 1;
     if (grid < min_grid) grid = min_grid;
-    hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream,
-                       reinterpret_cast<const uint32_t*>(codes), scales, n, n / block, elem_hist, scale_hist);
+    hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)grid), dim3(kHistThreads), 0, stream,
+                       codes, scales, n, n / block, elem_hist, scale_hist);
     return hipGetLastError();
 }
 

@@ -401,6 +401,28 @@ def test_histogram_full_size(oracle, mxq):
         assert int(eh.sum()) == x_np.size and int(sh.sum()) == x_np.size // block
 
 
+def test_histogram_unaligned_and_multi_pass(oracle, mxq):
+    """Pointers that are 4- but not 16-byte aligned (the kernel reads 128-bit vectors between a
+    serial head and tail), sizes around the vector and the grid-stride boundaries."""
+    rng = np.random.default_rng(77)
+    for rows, cols, block, c_off, s_off in [(1, 2, 2, 4, 4), (3, 34, 2, 4, 8), (7, 96, 16, 8, 12), (5, 1000, 4, 12, 4),
+                                            (640, 4096, 2, 4, 12), (2048, 8192, 16, 0, 4)]:
+        n = rows * cols
+        codes = rng.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)
+        scales = rng.integers(0, 256, size=(rows, cols // block), dtype=np.uint8)
+        cbuf = torch.zeros(n // 2 + 64, dtype=torch.uint8, device="cuda")
+        sbuf = torch.zeros(n // block + 64, dtype=torch.uint8, device="cuda")
+        c = cbuf[c_off:c_off + n // 2].view(rows, cols // 2)
+        s = sbuf[s_off:s_off + n // block].view(rows, cols // block)
+        c.copy_(torch.from_numpy(codes))
+        s.copy_(torch.from_numpy(scales))
+        assert c.data_ptr() % 16 == c_off % 16 and s.data_ptr() % 16 == s_off % 16
+        eh, sh = mxq.histogram(c, s, block)
+        weh, wsh = oracle.histograms(codes, scales)
+        assert (eh.cpu().numpy().astype(np.uint64) == weh).all(), (rows, cols, block)
+        assert (sh.cpu().numpy().astype(np.uint64) == wsh).all(), (rows, cols, block)
+
+
 # ------------------------------------------------------------------ graphs, very large tensors
 
 def test_graph_capture_and_replay(oracle, mxq):
