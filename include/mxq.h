@@ -107,6 +107,27 @@ MXQ_API int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
                  int x_dtype, void* stream);
 
 /*
+ * mxq_quantize_hier -- hierarchical scaling without a round trip to the host (the two-stage
+ * process of Section 2 as a dynamic activation tensor needs it): mxq_quantize with the
+ * per-tensor scale derived on the device from the tensor abs-max that mxq_tensor_absmax left
+ * in device memory,
+ *     T = mxq_tensor_scale_from_absmax(*absmax, elem_fmt, scale_fmt)      (the same bits),
+ * so that "abs-max, then quantise" is two launches on one stream with nothing in between, and
+ * a captured graph of the pair follows the data from replay to replay.
+ *
+ *   absmax            device, 1 float, 4-byte aligned; read when the kernel runs
+ *   tensor_scale_out  device, 1 float, 4-byte aligned, receives T (de-quantisation needs it);
+ *                     NULL to skip
+ * Everything else as for mxq_quantize.  rows*cols == 0 is a no-op that leaves
+ * tensor_scale_out untouched.  Errors as for mxq_quantize, plus INVALID_ARG for a NULL absmax.
+ */
+MXQ_API int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int block,
+                      int elem_fmt, int scale_fmt, int recipe,
+                      const float* absmax, float* tensor_scale_out,
+                      uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                      int x_dtype, void* stream);
+
+/*
  * mxq_dequantize -- x^_i = (q_i * S) * tensor_scale, rounded to nearest even into out_dtype
  * ("de-quantization simply multiplies by S", Section 2).
  *

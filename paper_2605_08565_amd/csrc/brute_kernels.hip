@@ -252,11 +252,19 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
 
 template <int DT, int B, int FMT, bool HAS_T, bool PRUNE>
 __global__ void __launch_bounds__(kThreads)
-brute_kernel(const void* __restrict__ x, int64_t n_full, float T,
+brute_kernel(const void* __restrict__ x, int64_t n_full, float T_arg,
+             const float* __restrict__ absmax_dev, float* __restrict__ t_out,
              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
+    float T = T_arg;
+    if constexpr (HAS_T) {
+        if (absmax_dev) {                                            // T from the abs-max in device memory
+            T = tensor_scale_of<FMT>(*absmax_dev);
+            if (t_out && blockIdx.x == 0 && threadIdx.x == 0) *t_out = T;
+        }
+    }
 
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     int64_t chunk = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -300,10 +308,18 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T,
 // Ragged tail (n not a multiple of 8; b = 2 or 4 only): lane 0 of one wavefront.
 template <int DT, int B, int FMT, bool HAS_T, bool PRUNE>
 __global__ void __launch_bounds__(64)
-brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T,
+brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T_arg,
+                  const float* __restrict__ absmax_dev, float* __restrict__ t_out,
                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
+    float T = T_arg;
+    if constexpr (HAS_T) {
+        if (absmax_dev) {
+            T = tensor_scale_of<FMT>(*absmax_dev);
+            if (t_out && threadIdx.x == 0) *t_out = T;      // t_out is passed only when no main kernel runs
+        }
+    }
     float v[8];
     load_partial<DT>(x, first, (threadIdx.x == 0) ? count : 0, v);
     if constexpr (HAS_T) {
@@ -328,27 +344,28 @@ static hipError_t launch_f(const StreamArgs& a)
 {
     const int64_t n_full = a.n / 8;
     const int count = (int)(a.n - n_full * 8);
-    const bool has_t = (a.T != 1.0f);
+    const bool has_t = (a.absmax_dev != nullptr) || (a.T != 1.0f);
     if (n_full > 0) {
         const int64_t need = (n_full + kThreads - 1) / kThreads;
         const dim3 grid((unsigned)(need < 256 * 8 ? need : 256 * 8)), block(kThreads);
         if (has_t)
             hipLaunchKernelGGL((brute_kernel<DT, B, FMT, true, PRUNE>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, (uint32_t*)a.codes, a.scales, a.sse);
+                               a.x, n_full, a.T, a.absmax_dev, a.t_out, (uint32_t*)a.codes, a.scales, a.sse);
         else
             hipLaunchKernelGGL((brute_kernel<DT, B, FMT, false, PRUNE>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, (uint32_t*)a.codes, a.scales, a.sse);
+                               a.x, n_full, a.T, a.absmax_dev, a.t_out, (uint32_t*)a.codes, a.scales, a.sse);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if constexpr (B < 8) {
         if (count > 0) {
+            float* t_out_tail = (n_full > 0) ? nullptr : a.t_out;
             if (has_t)
                 hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, true, PRUNE>), dim3(1), dim3(64), 0, a.stream,
-                                   a.x, n_full * 8, count, a.T, a.codes, a.scales, a.sse);
+                                   a.x, n_full * 8, count, a.T, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse);
             else
                 hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, false, PRUNE>), dim3(1), dim3(64), 0, a.stream,
-                                   a.x, n_full * 8, count, a.T, a.codes, a.scales, a.sse);
+                                   a.x, n_full * 8, count, a.T, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse);
         }
     }
     return hipGetLastError();

@@ -33,10 +33,13 @@ float host_scale_decode(int fmt, unsigned code)
 
 extern "C" {
 
-int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
-                 int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
-                 uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
-                 int x_dtype, void* stream)
+// Validation and launch shared by mxq_quantize (T by value) and mxq_quantize_hier (T derived on
+// the device from *absmax_dev).
+static int quantize_common(const void* x, int64_t rows, int64_t cols, int block,
+                           int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
+                           const float* absmax_dev, float* t_out,
+                           uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                           int x_dtype, void* stream)
 {
     if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
     if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
@@ -52,15 +55,36 @@ int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
     if (n >= ((int64_t)1 << 42)) return MXQ_ERR_UNSUPPORTED;        // 32-bit slice counters
     if (!x || !codes_out || !scales_out) return MXQ_ERR_INVALID_ARG;
     if (!aligned(x, 16) || !aligned(codes_out, 4) || !aligned(scales_out, 4) ||
-        (sse_out && !aligned(sse_out, 16)))
+        (sse_out && !aligned(sse_out, 16)) || !aligned(absmax_dev, 4) || !aligned(t_out, 4))
         return MXQ_ERR_ALIGNMENT;
 
     mxq::StreamArgs a;
     a.x = x; a.n = n; a.dtype = x_dtype; a.block = block; a.scale_fmt = scale_fmt;
-    a.recipe = recipe; a.T = tensor_scale; a.codes = codes_out; a.scales = scales_out;
+    a.recipe = recipe; a.T = tensor_scale; a.absmax_dev = absmax_dev; a.t_out = t_out;
+    a.codes = codes_out; a.scales = scales_out;
     a.sse = sse_out; a.stream = static_cast<hipStream_t>(stream);
     const hipError_t e = (recipe >= MXQ_RECIPE_BRUTE) ? mxq::launch_brute(a) : mxq::launch_stream(a);
     return e == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
+                 int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
+                 uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                 int x_dtype, void* stream)
+{
+    return quantize_common(x, rows, cols, block, elem_fmt, scale_fmt, recipe, tensor_scale, nullptr, nullptr,
+                           codes_out, scales_out, sse_out, x_dtype, stream);
+}
+
+int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int block,
+                      int elem_fmt, int scale_fmt, int recipe,
+                      const float* absmax, float* tensor_scale_out,
+                      uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                      int x_dtype, void* stream)
+{
+    if (!absmax) return MXQ_ERR_INVALID_ARG;
+    return quantize_common(x, rows, cols, block, elem_fmt, scale_fmt, recipe, 1.0f, absmax, tensor_scale_out,
+                           codes_out, scales_out, sse_out, x_dtype, stream);
 }
 
 int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,

@@ -78,6 +78,21 @@ __device__ __forceinline__ float scale_byte_value(int fmt, uint32_t code)
     return (code > (uint32_t)ScaleFmt<kUE5M3>::kMaxCode) ? nan : sf_decode<kUE5M3>(code);
 }
 
+// Per-tensor scale of hierarchical scaling (Section 2, two-stage process) from the tensor
+// abs-max: the abs-max lands on (largest element magnitude) x (largest scale value).  The same
+// float operations as the host helper of the C ABI, so both give the same bits; 1 for an
+// all-zero tensor or when the quotient vanishes (6 * 2^127 overflows for power-of-two scales).
+template <int FMT>
+__device__ __forceinline__ float tensor_scale_of(float absmax)
+{
+    float sf_max;
+    if constexpr (FMT == kE8M0) sf_max = u2f(254u << 23);
+    else sf_max = ScaleFmt<FMT>::kMaxValue;
+    if (!(absmax > 0.0f)) return 1.0f;
+    const float t = absmax / (6.0f * sf_max);
+    return (t > 0.0f && t < __builtin_inff()) ? t : 1.0f;
+}
+
 // ---------------------------------------------------------------------------------------
 // Quotients whose rounding decisions are exact.
 //

@@ -13,7 +13,9 @@ struct StreamArgs {
     const void* x;
     int64_t n;
     int dtype, block, scale_fmt, recipe;
-    float T;
+    float T;                   // per-tensor scale by value; ignored when absmax_dev is set
+    const float* absmax_dev;   // device: tensor abs-max from which the kernels derive T, or NULL
+    float* t_out;              // device: receives the derived T, or NULL
     uint8_t* codes;
     uint8_t* scales;
     float* sse;

@@ -144,7 +144,8 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
 // below its block's abs-max can still have |v/T| < 2^-78, where the remainder may underflow and
 // q1 be off by one ulp; nothing observes that: the element quantises to a signed zero and its
 // squared residual underflows to zero either way.
-enum : int { kNoT = 0, kFastT = 1, kSlowT = 2 };
+enum : int { kNoT = 0, kFastT = 1, kSlowT = 2, kDynT = 3 };   // kDynT: T comes from device memory, one of
+                                                              // the other three is chosen at run time
 
 __device__ __forceinline__ float div_by_T(float v, float T, float rT)
 {
@@ -165,22 +166,16 @@ __device__ __forceinline__ void block_amax(const float (&v)[8], float (&amax)[NB
     }
 }
 
-// Everything between the load and the store for one lane's 8 values.
-template <int B, int FMT, bool FOUR6, int TMODE>
-__device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, bool pz, const ScaleEntry* tab,
-                                              uint32_t& packed, uint32_t (&code_out)[(B < 8) ? 8 / B : 1],
-                                              float (&sse_sel)[4])
+// Division by the per-tensor scale (MODE: none / reciprocal-refined / plain) and the block
+// abs-max of the adjusted values.
+template <int MODE, int NBLK, int EPB, int LANES>
+__device__ __forceinline__ void adjust_and_amax(float (&v)[8], float T, float rT, float (&amax)[NBLK])
 {
-    constexpr int NBLK = (B < 8) ? 8 / B : 1;          // blocks inside one lane
-    constexpr int LANES = (B < 8) ? 1 : B / 8;         // lanes per block
-    constexpr int EPB = (B < 8) ? B : 8;               // elements of one block inside a lane
-
-    float amax[NBLK];
-    if constexpr (TMODE == kSlowT) {
+    if constexpr (MODE == kSlowT) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = v[i] / T;            // IEEE division
         block_amax<NBLK, EPB, LANES>(v, amax);
-    } else if constexpr (TMODE == kFastT) {
+    } else if constexpr (MODE == kFastT) {
         float raw[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) { raw[i] = v[i]; v[i] = div_by_T(raw[i], T, rT); }
@@ -196,6 +191,35 @@ __device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, 
         }
     } else {
         block_amax<NBLK, EPB, LANES>(v, amax);
+    }
+}
+
+// The reciprocal-refined division is exact for these T only (see div_by_T).
+__host__ __device__ inline bool fast_division_ok(float T)
+{
+    uint32_t tb;
+    __builtin_memcpy(&tb, &T, 4);
+    return T >= 0x1p-20f && T <= 0x1p20f && (tb & 0x7FFFFFu) != 0x7FFFFFu;
+}
+
+// Everything between the load and the store for one lane's 8 values.  `tdyn` (one of kNoT,
+// kFastT, kSlowT; wave-uniform) is read only when TMODE == kDynT.
+template <int B, int FMT, bool FOUR6, int TMODE>
+__device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, int tdyn, bool pz,
+                                              const ScaleEntry* tab, uint32_t& packed,
+                                              uint32_t (&code_out)[(B < 8) ? 8 / B : 1], float (&sse_sel)[4])
+{
+    constexpr int NBLK = (B < 8) ? 8 / B : 1;          // blocks inside one lane
+    constexpr int LANES = (B < 8) ? 1 : B / 8;         // lanes per block
+    constexpr int EPB = (B < 8) ? B : 8;               // elements of one block inside a lane
+
+    float amax[NBLK];
+    if constexpr (TMODE == kDynT) {
+        if (tdyn == kNoT) adjust_and_amax<kNoT, NBLK, EPB, LANES>(v, T, rT, amax);
+        else if (tdyn == kFastT) adjust_and_amax<kFastT, NBLK, EPB, LANES>(v, T, rT, amax);
+        else adjust_and_amax<kSlowT, NBLK, EPB, LANES>(v, T, rT, amax);
+    } else {
+        adjust_and_amax<TMODE, NBLK, EPB, LANES>(v, T, rT, amax);
     }
 
     float sq[8];
@@ -358,7 +382,7 @@ template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChunk<DT> (&nxt)[kItems],
                                             TileOut<B> (&out)[kItems], bool have_prev, uint32_t s_prev,
                                             const void* __restrict__ x, uint32_t s0, uint32_t stride,
-                                            Slices sl, float T, float rT, bool pz, const ScaleEntry* tab,
+                                            Slices sl, float T, float rT, int tdyn, bool pz, const ScaleEntry* tab,
                                             u32x4* wave_lds, uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
                                             float* __restrict__ sse_out)
 {
@@ -375,14 +399,15 @@ __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChun
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kItems; ++i)
-        process_chunk<B, FMT, FOUR6, TMODE>(v[i], T, rT, pz, tab, out[i].packed, out[i].code, out[i].sse);
+        process_chunk<B, FMT, FOUR6, TMODE>(v[i], T, rT, tdyn, pz, tab, out[i].packed, out[i].code, out[i].sse);
 }
 
 // Main kernel: the complete chunks, grid-stride over workgroup tiles with two register buffers
 // alternating between "being processed" and "in flight".
 template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __global__ void __launch_bounds__(kThreads)
-stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunks, float T, int pz,
+stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunks, float T_arg, int pz,
+              const float* __restrict__ absmax_dev, float* __restrict__ t_out,
               uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
@@ -393,6 +418,13 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
     const uint32_t stride = gridDim.x * (uint32_t)kItems;
     uint32_t s0 = blockIdx.x * (uint32_t)kItems;
     if (s0 >= sl.count) return;                                      // whole workgroup
+    float T = T_arg;
+    int tdyn = TMODE;
+    if constexpr (TMODE == kDynT) {                                  // T from the abs-max left in device memory
+        T = tensor_scale_of<FMT>(*absmax_dev);
+        tdyn = (T == 1.0f) ? kNoT : (fast_division_ok(T) ? kFastT : kSlowT);
+        if (t_out && blockIdx.x == 0 && threadIdx.x == 0) *t_out = T;
+    }
     const float rT = 1.0f / T;                                       // correctly rounded
 
     // the first tile's loads are in flight while the scale table is built
@@ -406,13 +438,13 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
     uint32_t s_prev = s0;
     while (true) {
         stream_step<DT, B, FMT, FOUR6, TMODE>(bufA, bufB, out, have_prev, s_prev, x, s0, stride, sl,
-                                              T, rT, pz != 0, tab, wave_lds, codes, scales, sse_out);
+                                              T, rT, tdyn, pz != 0, tab, wave_lds, codes, scales, sse_out);
         have_prev = true;
         s_prev = s0;
         s0 += stride;
         if (s0 >= sl.count) break;
         stream_step<DT, B, FMT, FOUR6, TMODE>(bufB, bufA, out, true, s_prev, x, s0, stride, sl,
-                                              T, rT, pz != 0, tab, wave_lds, codes, scales, sse_out);
+                                              T, rT, tdyn, pz != 0, tab, wave_lds, codes, scales, sse_out);
         s_prev = s0;
         s0 += stride;
         if (s0 >= sl.count) break;
@@ -425,7 +457,8 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
 // `count` < 8 elements are handled by lane 0 of one wavefront, reading and writing element-wise.
 template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __global__ void __launch_bounds__(64)
-stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T, int pz,
+stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T_arg, int pz,
+                   const float* __restrict__ absmax_dev, float* __restrict__ t_out,
                    uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
 {
     constexpr int NBLK = (B < 8) ? 8 / B : 1;
@@ -435,7 +468,14 @@ stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T
     float v[8], sse_sel[4];
     uint32_t packed, code_out[NBLK];
     load_partial<DT>(x, first, (threadIdx.x == 0) ? count : 0, v);
-    process_chunk<B, FMT, FOUR6, TMODE>(v, T, 1.0f / T, pz != 0, tab, packed, code_out, sse_sel);
+    float T = T_arg;
+    int tdyn = TMODE;
+    if constexpr (TMODE == kDynT) {
+        T = tensor_scale_of<FMT>(*absmax_dev);
+        tdyn = (T == 1.0f) ? kNoT : kSlowT;
+        if (t_out && threadIdx.x == 0) *t_out = T;      // t_out is passed only when no main kernel runs
+    }
+    process_chunk<B, FMT, FOUR6, TMODE>(v, T, 1.0f / T, tdyn, pz != 0, tab, packed, code_out, sse_sel);
     if (threadIdx.x != 0) return;
     for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
     if constexpr (B < 8) {
@@ -455,38 +495,36 @@ static hipError_t launch_recipe(const StreamArgs& a, int pz)
 {
     const int64_t n_full = a.n / 8;
     const int count = (int)(a.n - n_full * 8);
-    // reciprocal-refined division only where its exactness argument holds
-    uint32_t tb;
-    static_assert(sizeof(tb) == sizeof(a.T), "");
-    __builtin_memcpy(&tb, &a.T, 4);
-    const bool fast_t = a.T >= 0x1p-20f && a.T <= 0x1p20f && (tb & 0x7FFFFFu) != 0x7FFFFFu;
-    const int tmode = (a.T == 1.0f) ? kNoT : (fast_t ? kFastT : kSlowT);
+    // reciprocal-refined division only where its exactness argument holds; with the abs-max in
+    // device memory the kernel makes the same choice itself
+    const int tmode = a.absmax_dev ? kDynT : (a.T == 1.0f) ? kNoT : (fast_division_ok(a.T) ? kFastT : kSlowT);
     if (n_full > 0) {
         const int64_t slices = (n_full + kThreads - 1) / kThreads;
         const uint32_t n_slices = (uint32_t)slices;
         const uint32_t last = (uint32_t)(n_full - (slices - 1) * kThreads);
         const dim3 grid(stream_grid(((slices + kItems - 1) / kItems) * kThreads)), block(kThreads);
         uint32_t* codes = reinterpret_cast<uint32_t*>(a.codes);
-        if (tmode == kNoT)
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kNoT>), grid, block, 0, a.stream,
-                               a.x, n_slices, last, a.T, pz, codes, a.scales, a.sse);
-        else if (tmode == kFastT)
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kFastT>), grid, block, 0, a.stream,
-                               a.x, n_slices, last, a.T, pz, codes, a.scales, a.sse);
-        else
-            hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, kSlowT>), grid, block, 0, a.stream,
-                               a.x, n_slices, last, a.T, pz, codes, a.scales, a.sse);
+#define MXQ_LAUNCH_STREAM(MODE)                                                                       \
+    hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, MODE>), grid, block, 0, a.stream, a.x, n_slices,    \
+                       last, a.T, pz, a.absmax_dev, a.t_out, codes, a.scales, a.sse)
+        if (tmode == kNoT) MXQ_LAUNCH_STREAM(kNoT);
+        else if (tmode == kFastT) MXQ_LAUNCH_STREAM(kFastT);
+        else if (tmode == kSlowT) MXQ_LAUNCH_STREAM(kSlowT);
+        else MXQ_LAUNCH_STREAM(kDynT);
+#undef MXQ_LAUNCH_STREAM
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if constexpr (B < 8) {
         if (count > 0) {
-            if (tmode != kNoT)
-                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, kSlowT>), dim3(1), dim3(64), 0, a.stream,
-                                   a.x, n_full * 8, count, a.T, pz, a.codes, a.scales, a.sse);
-            else
-                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, kNoT>), dim3(1), dim3(64), 0, a.stream,
-                                   a.x, n_full * 8, count, a.T, pz, a.codes, a.scales, a.sse);
+            float* t_out_tail = (n_full > 0) ? nullptr : a.t_out;
+#define MXQ_LAUNCH_TAIL(MODE)                                                                         \
+    hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, MODE>), dim3(1), dim3(64), 0, a.stream, a.x,   \
+                       n_full * 8, count, a.T, pz, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse)
+            if (tmode == kDynT) MXQ_LAUNCH_TAIL(kDynT);
+            else if (tmode != kNoT) MXQ_LAUNCH_TAIL(kSlowT);
+            else MXQ_LAUNCH_TAIL(kNoT);
+#undef MXQ_LAUNCH_TAIL
         }
     }
     return hipGetLastError();

@@ -41,6 +41,8 @@ def lib() -> ctypes.CDLL:
     i64, i32, f32, vp, u8 = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_uint8
     L.mxq_quantize.restype = i32
     L.mxq_quantize.argtypes = [vp, i64, i64, i32, i32, i32, i32, f32, vp, vp, vp, i32, vp]
+    L.mxq_quantize_hier.restype = i32
+    L.mxq_quantize_hier.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
     L.mxq_dequantize.restype = i32
     L.mxq_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
     L.mxq_tensor_absmax.restype = i32
@@ -121,6 +123,39 @@ def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_sc
                               sse_out.data_ptr() if sse_out is not None else None,
                               _dtype_code(x), _stream_ptr(stream)))
     return codes_out, scales_out, sse_out
+
+
+def quantize_hier(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, absmax: torch.Tensor,
+                  tensor_scale_out: torch.Tensor | None = None,
+                  codes_out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None,
+                  sse_out: torch.Tensor | None = None, want_sse: bool = True, stream=None,
+                  elem_fmt: int = ELEM_E2M1):
+    """mxq_quantize_hier: T is derived on the device from `absmax` (the one-element tensor that
+    tensor_absmax wrote).  Returns (codes, scales, sse, tensor_scale) -- the last a one-element
+    fp32 device tensor."""
+    if not x.is_cuda or x.dim() != 2 or not x.is_contiguous():
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, cols = x.shape
+    dev = x.device
+    if codes_out is None:
+        codes_out = torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev)
+    if scales_out is None:
+        scales_out = torch.empty((rows, cols // block if block > 0 else 0), dtype=torch.uint8, device=dev)
+    if sse_out is None and want_sse:
+        sse_out = torch.empty((rows, cols // block if block > 0 else 0), dtype=torch.float32, device=dev)
+    if tensor_scale_out is None:
+        tensor_scale_out = torch.ones(1, dtype=torch.float32, device=dev)
+    _need(absmax, 4, "absmax", torch.float32)
+    _need(tensor_scale_out, 4, "tensor_scale_out", torch.float32)
+    _need(codes_out, rows * cols // 2, "codes_out", torch.uint8)
+    _need(scales_out, _nblocks(rows, cols, block), "scales_out", torch.uint8)
+    if sse_out is not None:
+        _need(sse_out, 4 * _nblocks(rows, cols, block), "sse_out", torch.float32)
+    _check(lib().mxq_quantize_hier(x.data_ptr(), rows, cols, block, elem_fmt, scale_fmt, recipe,
+                                   absmax.data_ptr(), tensor_scale_out.data_ptr(), codes_out.data_ptr(),
+                                   scales_out.data_ptr(), sse_out.data_ptr() if sse_out is not None else None,
+                                   _dtype_code(x), _stream_ptr(stream)))
+    return codes_out, scales_out, sse_out, tensor_scale_out
 
 
 def dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt: int,

@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_dequantize", "mxq_tensor_absmax", "mxq_clip_sse",
+    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_tensor_absmax", "mxq_clip_sse",
                             "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
                             "mxq_num_candidates", "mxq_status_string"])
@@ -86,6 +86,15 @@ def test_argument_validation_without_a_launch(mxq):
     assert q(rows=0) == mxq.OK
     assert q(rows=0, x=None, codes=None, scales=None, sse=None) == mxq.OK
     assert q(rows=3, cols=0) == mxq.OK
+
+    def qh(x=P, rows=4, cols=64, block=16, elem=0, fmt=1, rec=0, amax=P, t_out=P, codes=P, scales=P, sse=P, dt=0):
+        return L.mxq_quantize_hier(x, rows, cols, block, elem, fmt, rec, amax, t_out, codes, scales, sse, dt, None)
+
+    assert qh(amax=None) == mxq.ERR_INVALID_ARG
+    assert qh(x=None) == mxq.ERR_INVALID_ARG and qh(block=3) == mxq.ERR_INVALID_ARG
+    assert qh(fmt=0, rec=4) == mxq.ERR_UNSUPPORTED
+    assert qh(amax=P + 2) == mxq.ERR_ALIGNMENT and qh(t_out=P + 1) == mxq.ERR_ALIGNMENT
+    assert qh(rows=0) == mxq.OK and qh(rows=0, t_out=None) == mxq.OK
 
     def d(codes=P, scales=P, rows=4, cols=64, block=16, elem=0, fmt=1, T=1.0, out=P, dt=1):
         return L.mxq_dequantize(codes, scales, rows, cols, block, elem, fmt, T, out, dt, None)

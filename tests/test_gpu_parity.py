@@ -89,6 +89,41 @@ def test_hierarchical_small(oracle, mxq, block):
           tag="hierarchical-f32")
 
 
+def check_hier(oracle, mxq, x_np, block, fmt, rec, tag=""):
+    """mxq_quantize_hier against the oracle run with the oracle's own T."""
+    print(f"[parity] hier-device {tag} shape={x_np.shape} dtype={x_np.dtype} b={block} "
+          f"fmt={FMT_NAMES[fmt]} recipe={REC_NAMES[rec]}", flush=True)
+    x = mxq.from_bits(x_np)
+    amax = mxq.tensor_absmax(x)
+    gc, gs, ge, gT = mxq.quantize_hier(x, block, fmt, rec, amax)
+    torch.cuda.synchronize()
+    T = np.float32(oracle.tensor_scale(oracle.tensor_absmax(x_np), fmt))
+    assert gT.cpu().numpy().view(np.uint32)[0] == T.view(np.uint32), (float(gT.cpu()[0]), float(T))
+    oc, os_, oe = oracle.quantize(x_np, block, fmt, ORACLE_REC[rec], tensor_scale=float(T))
+    assert (gs.cpu().numpy() == os_).all() and (gc.cpu().numpy() == oc).all()
+    assert (ge.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("block", (2, 4, 16, 128))
+def test_hierarchical_scale_taken_from_device_memory(oracle, mxq, block):
+    """The per-tensor scale derived by the kernels from the abs-max in device memory: every
+    division path (T = 1 for a zero tensor and for power-of-two scales, the reciprocal-refined
+    range, plain division beyond it), ragged sizes whose only launch is the tail kernel, fp32."""
+    acts = W.outlier_activations(48, 1024, seed=700 + block)
+    huge = (W.normal_f32(9, 256, seed=701, sigma=1.0) * np.float32(1e30)).astype(np.float32)   # T > 2^20
+    tiny = (W.normal_f32(9, 256, seed=702, sigma=1.0) * np.float32(1e-12)).astype(np.float32)  # T < 2^-20
+    zeros = np.zeros((4, 256), np.float32)
+    for x_np, tag in ((acts, "activations"), (W.bf16_bits_to_f32(acts), "activations-f32"), (huge, "huge"),
+                      (tiny, "tiny"), (zeros, "zeros")):
+        for fmt, rec in ((1, 0), (1, 2), (1, 3), (2, 0), (2, 2), (0, 0), (1, 4), (2, 5)):
+            check_hier(oracle, mxq, x_np, block, fmt, rec, tag)
+    if block <= 4:
+        for shape in ((5, 12), (1, 4)):                     # 60 elements: main + tail; 4: tail only
+            x_np = W.normal_f32(shape[0], shape[1], seed=703, sigma=0.3)
+            for fmt, rec in ((1, 0), (1, 2), (2, 4), (0, 0)):
+                check_hier(oracle, mxq, x_np, block, fmt, rec, "ragged")
+
+
 def test_hierarchical_division_paths(oracle, mxq):
     """The per-tensor division has a reciprocal-refined path (2^-20 <= T <= 2^20), a per-wavefront
     fall-back for blocks of very small or very large adjusted values, and a plain-division path
@@ -426,7 +461,8 @@ def test_histogram_unaligned_and_multi_pass(oracle, mxq):
 # ------------------------------------------------------------------ graphs, very large tensors
 
 def test_graph_capture_and_replay(oracle, mxq):
-    """The whole path (tensor abs-max, quantise, de-quantise, clip SSE, histogram) captured in
+    """The whole path (tensor abs-max, hierarchical quantise with the scale taken from device
+    memory, quantise, de-quantise, clip SSE) captured in
     a HIP graph and replayed with new input contents between replays, with eager work and
     synchronisation in between; every replay must equal the oracle on the current contents."""
     rows, cols, block = 64, 1024, 16
@@ -437,6 +473,8 @@ def test_graph_capture_and_replay(oracle, mxq):
     sse = torch.empty((rows, cols // block), dtype=torch.float32, device="cuda")
     deq = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
     clip = torch.empty((rows, cols // block), dtype=torch.float32, device="cuda")
+    codes_h, scales_h, sse_h = torch.empty_like(codes), torch.empty_like(scales), torch.empty_like(sse)
+    t_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):                      # warm-up outside capture
@@ -446,6 +484,8 @@ def test_graph_capture_and_replay(oracle, mxq):
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         mxq.tensor_absmax(x, out=amax)
+        mxq.quantize_hier(x, block, 1, 2, amax, tensor_scale_out=t_dev, codes_out=codes_h, scales_out=scales_h,
+                          sse_out=sse_h)
         mxq.quantize(x, block, 1, 2, codes_out=codes, scales_out=scales, sse_out=sse)
         mxq.dequantize(codes, scales, block, 1, 1.0, out=deq)
         mxq.clip_sse(x, scales, block, 1, out=clip)
@@ -462,6 +502,12 @@ def test_graph_capture_and_replay(oracle, mxq):
         want = oracle.dequantize(oc, os_, block, 1, 1.0, oracle.DT_BF16)
         assert (deq.cpu().view(torch.int16).numpy().view(np.uint16) == want).all()
         assert (clip.cpu().numpy().view(np.uint32) == oracle.clip_sse(x_np, os_, block, 1).view(np.uint32)).all()
+        # hierarchical scaling inside the graph: T follows the data from replay to replay
+        T = np.float32(oracle.tensor_scale(oracle.tensor_absmax(x_np), 1))
+        assert t_dev.cpu().numpy().view(np.uint32)[0] == T.view(np.uint32)
+        hc, hs, he = oracle.quantize(x_np, block, 1, 2, tensor_scale=float(T))
+        assert (codes_h.cpu().numpy() == hc).all() and (scales_h.cpu().numpy() == hs).all()
+        assert (sse_h.cpu().numpy().view(np.uint32) == he.view(np.uint32)).all()
         # eager work between replays
         e = mxq.quantize(x, block, 1, 0)[2]
         assert bool((e >= sse).all())
