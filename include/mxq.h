@@ -141,6 +141,17 @@ MXQ_API int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
                    void* x_out, int out_dtype, void* stream);
 
 /*
+ * mxq_dequantize_hier -- mxq_dequantize with the per-tensor scale read from device memory (the
+ * word mxq_quantize_hier wrote to tensor_scale_out) when the kernel runs.
+ *   tensor_scale   device, 1 float, 4-byte aligned
+ * Errors as for mxq_dequantize, plus INVALID_ARG for a NULL tensor_scale.
+ */
+MXQ_API int mxq_dequantize_hier(const uint8_t* codes, const uint8_t* scales,
+                        int64_t rows, int64_t cols, int block,
+                        int elem_fmt, int scale_fmt, const float* tensor_scale,
+                        void* x_out, int out_dtype, void* stream);
+
+/*
  * mxq_tensor_absmax -- first stage of hierarchical scaling (Section 2): max |x_i| over the
  * whole tensor, written as one float to absmax_out (device, 4-byte aligned).  x 16-byte
  * aligned.  An empty tensor writes 0.

@@ -20,8 +20,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 template <int B>
 __global__ void __launch_bounds__(kThreads)
 dequant_bf16_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
-                    int fmt, float T, uint16_t* __restrict__ out)
+                    int fmt, float T_arg, const float* __restrict__ t_dev, uint16_t* __restrict__ out)
 {
+    const float T = t_dev ? *t_dev : T_arg;                         // per-tensor scale by value or from device memory
     constexpr int NBLK = (B < 8) ? 8 / B : 1;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
     constexpr int EPB = (B < 8) ? B : 8;
@@ -70,8 +71,9 @@ dequant_bf16_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restric
 template <int B>
 __global__ void __launch_bounds__(kThreads)
 dequant_f32_kernel(const uint16_t* __restrict__ codes, const uint8_t* __restrict__ scales, int64_t n,
-                   int fmt, float T, float* __restrict__ out)
+                   int fmt, float T_arg, const float* __restrict__ t_dev, float* __restrict__ out)
 {
+    const float T = t_dev ? *t_dev : T_arg;
     constexpr int NBLK = (B < 4) ? 4 / B : 1;
     constexpr int EPB = (B < 4) ? B : 4;
     const int64_t n_half = (n + 3) >> 2;
@@ -109,7 +111,7 @@ static void launch_dequant_f32(const DequantArgs& a)
     const int grid = stream_grid((a.n + 3) / 4);
 #define MXQ_DQF(BB)                                                                                  \
     hipLaunchKernelGGL((dequant_f32_kernel<BB>), dim3(grid), dim3(kThreads), 0, a.stream,           \
-                       (const uint16_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, (float*)a.out)
+                       (const uint16_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, a.t_dev, (float*)a.out)
     switch (a.block) {
         case 2: MXQ_DQF(2); break;
         case 4: MXQ_DQF(4); break;
@@ -127,7 +129,7 @@ static void launch_dequant_bf16(const DequantArgs& a)
     const int grid = stream_grid((a.n + 7) / 8);
 #define MXQ_DQ(BB)                                                                                   \
     hipLaunchKernelGGL((dequant_bf16_kernel<BB>), dim3(grid), dim3(kThreads), 0, a.stream,          \
-                       (const uint32_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, (uint16_t*)a.out)
+                       (const uint32_t*)a.codes, a.scales, a.n, a.scale_fmt, a.T, a.t_dev, (uint16_t*)a.out)
     switch (a.block) {
         case 2: MXQ_DQ(2); break;
         case 4: MXQ_DQ(4); break;

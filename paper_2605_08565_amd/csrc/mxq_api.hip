@@ -87,10 +87,10 @@ int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int block,
                            codes_out, scales_out, sse_out, x_dtype, stream);
 }
 
-int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
-                   int64_t rows, int64_t cols, int block,
-                   int elem_fmt, int scale_fmt, float tensor_scale,
-                   void* x_out, int out_dtype, void* stream)
+static int dequantize_common(const uint8_t* codes, const uint8_t* scales,
+                             int64_t rows, int64_t cols, int block,
+                             int elem_fmt, int scale_fmt, float tensor_scale, const float* t_dev,
+                             void* x_out, int out_dtype, void* stream)
 {
     if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
     if (!valid_block(block) || cols % block != 0) return MXQ_ERR_INVALID_ARG;
@@ -102,12 +102,33 @@ int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
     const int64_t n = rows * cols;
     if (n == 0) return MXQ_OK;
     if (!codes || !scales || !x_out) return MXQ_ERR_INVALID_ARG;
-    if (!aligned(codes, 4) || !aligned(scales, 4) || !aligned(x_out, 16)) return MXQ_ERR_ALIGNMENT;
+    if (!aligned(codes, 4) || !aligned(scales, 4) || !aligned(x_out, 16) || !aligned(t_dev, 4))
+        return MXQ_ERR_ALIGNMENT;
 
     mxq::DequantArgs a;
     a.codes = codes; a.scales = scales; a.n = n; a.block = block; a.scale_fmt = scale_fmt;
-    a.dtype = out_dtype; a.T = tensor_scale; a.out = x_out; a.stream = static_cast<hipStream_t>(stream);
+    a.dtype = out_dtype; a.T = tensor_scale; a.t_dev = t_dev; a.out = x_out;
+    a.stream = static_cast<hipStream_t>(stream);
     return mxq::launch_dequant(a) == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+int mxq_dequantize(const uint8_t* codes, const uint8_t* scales,
+                   int64_t rows, int64_t cols, int block,
+                   int elem_fmt, int scale_fmt, float tensor_scale,
+                   void* x_out, int out_dtype, void* stream)
+{
+    return dequantize_common(codes, scales, rows, cols, block, elem_fmt, scale_fmt, tensor_scale, nullptr,
+                             x_out, out_dtype, stream);
+}
+
+int mxq_dequantize_hier(const uint8_t* codes, const uint8_t* scales,
+                        int64_t rows, int64_t cols, int block,
+                        int elem_fmt, int scale_fmt, const float* tensor_scale,
+                        void* x_out, int out_dtype, void* stream)
+{
+    if (!tensor_scale) return MXQ_ERR_INVALID_ARG;
+    return dequantize_common(codes, scales, rows, cols, block, elem_fmt, scale_fmt, 1.0f, tensor_scale,
+                             x_out, out_dtype, stream);
 }
 
 int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,

@@ -27,7 +27,8 @@ struct DequantArgs {
     const uint8_t* scales;
     int64_t n;
     int block, scale_fmt, dtype;
-    float T;
+    float T;                   // per-tensor scale by value; ignored when t_dev is set
+    const float* t_dev;        // device: per-tensor scale, or NULL
     void* out;
     hipStream_t stream;
 };

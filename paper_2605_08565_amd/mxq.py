@@ -45,6 +45,8 @@ def lib() -> ctypes.CDLL:
     L.mxq_quantize_hier.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
     L.mxq_dequantize.restype = i32
     L.mxq_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
+    L.mxq_dequantize_hier.restype = i32
+    L.mxq_dequantize_hier.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, i32, vp]
     L.mxq_tensor_absmax.restype = i32
     L.mxq_tensor_absmax.argtypes = [vp, i64, i64, i32, vp, vp]
     L.mxq_clip_sse.restype = i32
@@ -159,8 +161,10 @@ def quantize_hier(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, absm
 
 
 def dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt: int,
-               tensor_scale: float = 1.0, out_dtype: torch.dtype = torch.float32,
+               tensor_scale=1.0, out_dtype: torch.dtype = torch.float32,
                out: torch.Tensor | None = None, stream=None, elem_fmt: int = ELEM_E2M1) -> torch.Tensor:
+    """mxq_dequantize; with a one-element fp32 device tensor as `tensor_scale` (as returned by
+    quantize_hier) mxq_dequantize_hier, which reads the scale on the device."""
     rows, half = codes.shape
     cols = half * 2
     if out is None:
@@ -168,6 +172,12 @@ def dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt:
     _need(codes, rows * half, "codes", torch.uint8)
     _need(scales, _nblocks(rows, cols, block), "scales", torch.uint8)
     _need(out, rows * cols * out.element_size(), "out")
+    if isinstance(tensor_scale, torch.Tensor):
+        _need(tensor_scale, 4, "tensor_scale", torch.float32)
+        _check(lib().mxq_dequantize_hier(codes.data_ptr(), scales.data_ptr(), rows, cols, block, elem_fmt,
+                                         scale_fmt, tensor_scale.data_ptr(), out.data_ptr(), _dtype_code(out),
+                                         _stream_ptr(stream)))
+        return out
     _check(lib().mxq_dequantize(codes.data_ptr(), scales.data_ptr(), rows, cols, block, elem_fmt,
                                 scale_fmt, float(tensor_scale), out.data_ptr(), _dtype_code(out),
                                 _stream_ptr(stream)))

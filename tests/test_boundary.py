@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_tensor_absmax", "mxq_clip_sse",
+    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_clip_sse",
                             "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
                             "mxq_num_candidates", "mxq_status_string"])
@@ -107,6 +107,12 @@ def test_argument_validation_without_a_launch(mxq):
     assert d(T=0.0) == mxq.ERR_INVALID_ARG
     assert d(out=P + 8) == mxq.ERR_ALIGNMENT
     assert d(rows=0) == mxq.OK
+
+    def dh(codes=P, scales=P, rows=4, cols=64, block=16, elem=0, fmt=1, t=P, out=P, dt=1):
+        return L.mxq_dequantize_hier(codes, scales, rows, cols, block, elem, fmt, t, out, dt, None)
+
+    assert dh(t=None) == mxq.ERR_INVALID_ARG and dh(codes=None) == mxq.ERR_INVALID_ARG
+    assert dh(t=P + 2) == mxq.ERR_ALIGNMENT and dh(rows=0) == mxq.OK
 
     def cl(x=P, scales=P, rows=4, cols=64, block=16, elem=0, fmt=1, T=1.0, out=P, dt=0):
         return L.mxq_clip_sse(x, scales, rows, cols, block, elem, fmt, T, out, dt, None)

@@ -102,6 +102,14 @@ def check_hier(oracle, mxq, x_np, block, fmt, rec, tag=""):
     oc, os_, oe = oracle.quantize(x_np, block, fmt, ORACLE_REC[rec], tensor_scale=float(T))
     assert (gs.cpu().numpy() == os_).all() and (gc.cpu().numpy() == oc).all()
     assert (ge.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
+    # de-quantise with the scale still in device memory
+    for dt, tdt in ((oracle.DT_F32, torch.float32), (oracle.DT_BF16, torch.bfloat16)):
+        got = mxq.dequantize(gc, gs, block, fmt, gT, tdt).cpu()
+        want = oracle.dequantize(oc, os_, block, fmt, float(T), dt)
+        if tdt == torch.float32:
+            assert (got.numpy().view(np.uint32) == want.view(np.uint32)).all()
+        else:
+            assert (got.view(torch.int16).numpy().view(np.uint16) == want).all()
 
 
 @pytest.mark.parametrize("block", (2, 4, 16, 128))
