@@ -230,6 +230,32 @@ def test_special_values(oracle, mxq):
             check(oracle, mxq, xb, block, fmt, rec, tag="special-bf16")
 
 
+def test_randomised_wide_dynamic_range(oracle, mxq):
+    """Seeded random tensors whose magnitudes spread over many binades (log-uniform exponents,
+    per-row and per-element), with zeros and repeated values mixed in, under random per-tensor
+    scales: every recipe, both dtypes.  Stresses the scale-format limits, the pruning bounds of
+    the pruned search and the fall-backs of the per-tensor division."""
+    rng = np.random.default_rng(20260508)
+    for case in range(30):
+        rows, cols = int(rng.integers(3, 20)), 128 * int(rng.integers(1, 5))
+        row_exp = rng.uniform(-36, 30, size=(rows, 1))
+        elem_exp = rng.uniform(-6, 6, size=(rows, cols)) * rng.integers(0, 2, size=(rows, 1))
+        x = (rng.standard_normal((rows, cols)) * np.exp2(row_exp + elem_exp)).astype(np.float32)
+        x[rng.random((rows, cols)) < 0.05] = 0.0
+        x[rng.random((rows, cols)) < 0.05] *= -1.0
+        rep = rng.random((rows, cols)) < 0.1
+        x[rep] = np.float32(x[0, 0])
+        T = float(np.float32(np.exp2(rng.uniform(-30, 30)))) if case % 2 else 1.0
+        data = x if case % 3 else W.f32_to_bf16_bits(x)
+        with np.errstate(over="ignore", divide="ignore", invalid="ignore"):
+            adj = np.abs(W.bf16_bits_to_f32(data) if data.dtype == np.uint16 else data).astype(np.float64) / T
+        if not np.isfinite(adj.astype(np.float32)).all():        # adjusted inputs must stay finite
+            T = 1.0
+        for block in (2, 4, 8, 16, 32, 64, 128)[case % 3::3]:
+            for fmt, rec in combos():
+                check(oracle, mxq, data, block, fmt, rec, T=T if fmt else 1.0, tag=f"random-{case}")
+
+
 def test_sse_out_may_be_null(oracle, mxq):
     x_np = W.student_t_weights(16, 256, seed=5)
     x = mxq.from_bits(x_np)
