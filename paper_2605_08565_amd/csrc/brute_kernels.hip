@@ -8,8 +8,9 @@
 // rounding, so the quotient v / S is formed once per mantissa (w_m = v / m, 7 divisions per
 // element instead of one per candidate) and the E2M1 conversion instruction applies 2^e.
 // The inverse conversion returns q * 2^e, and the residual v - (q * 2^e) * m needs a single
-// FMA because the product is exact.  Candidates are visited in ascending code order, so a
-// strict "less than" keeps the lowest code on ties.
+// FMA because the product is exact.  Candidates are visited in ascending code order, one
+// binade (8 codes) at a time, so a strict "less than" between binades and the first position
+// inside one keep the lowest code on ties.
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"
 
@@ -32,41 +33,58 @@ struct BruteState {
     uint32_t best_code[NBLK];
 };
 
-// Arg-min inside one group of up to 8 consecutive codes: the running minimum and the position
-// (0..7, 8 = none yet) of the first candidate of the group that improved on it.  The position is
-// an inline constant of the select instruction, so a candidate costs compare + two selects.
+// Arg-min over a group of up to 8 consecutive codes (one binade): begin(), put<POS>(k, sse) per
+// candidate and block slot, end(st, code0) -- the code of position p is code0 + p.  The
+// candidates only deposit their block SSEs; the group's minimum (three-input minimum
+// instructions) is compared with the running best once per group, and only when some lane of
+// the wavefront improved is the position of the minimum looked up (the first position that
+// equals it: the lowest code on a tie inside the group; between groups "strictly less" keeps
+// the earlier, lower code).  A candidate costs half an instruction here; measured against a
+// compare and two selects per candidate it is faster also when most groups improve (the
+// pruned search).
 template <int B>
-struct GroupBest {
+struct GroupArgMin {
     static constexpr int NBLK = BruteState<B>::NBLK;
-    float sse[NBLK];
-    uint32_t pos[NBLK];
+    float s[NBLK][8];
+
+    // Position 7 is the only one that can be without a candidate (the 7 sub-normal codes; the
+    // NaN code at the top of the last binade): +inf never wins.
+    __device__ __forceinline__ void begin()
+    {
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) s[k][7] = __builtin_inff();
+    }
+    template <int POS>
+    __device__ __forceinline__ void put(int k, float sse) { s[k][POS] = sse; }
+    __device__ __forceinline__ void end(BruteState<B>& st, uint32_t code0) const
+    {
+        float gmin[NBLK];
+        bool any = false;
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) {
+            const float a = fminf(fminf(s[k][0], s[k][1]), s[k][2]);
+            const float b = fminf(fminf(s[k][3], s[k][4]), s[k][5]);
+            gmin[k] = fminf(fminf(a, b), fminf(s[k][6], s[k][7]));
+            any |= gmin[k] < st.best_sse[k];
+        }
+        if (__builtin_amdgcn_ballot_w64(any) == 0ull) return;           // wave-uniform
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) {
+            uint32_t pos = 7u;
+#pragma unroll
+            for (int i = 6; i >= 0; --i) pos = (s[k][i] == gmin[k]) ? (uint32_t)i : pos;
+            const bool better = gmin[k] < st.best_sse[k];
+            st.best_code[k] = better ? code0 + pos : st.best_code[k];
+            st.best_sse[k] = better ? gmin[k] : st.best_sse[k];
+        }
+    }
 };
 
-template <int B>
-__device__ __forceinline__ void group_begin(const BruteState<B>& st, GroupBest<B>& g)
-{
-#pragma unroll
-    for (int k = 0; k < GroupBest<B>::NBLK; ++k) { g.sse[k] = st.best_sse[k]; g.pos[k] = 8u; }
-}
-
-// code of position p in the group is code0 + p
-template <int B>
-__device__ __forceinline__ void group_end(BruteState<B>& st, const GroupBest<B>& g, uint32_t code0)
-{
-#pragma unroll
-    for (int k = 0; k < GroupBest<B>::NBLK; ++k) {
-        st.best_code[k] = (g.pos[k] != 8u) ? code0 + g.pos[k] : st.best_code[k];
-        st.best_sse[k] = g.sse[k];
-    }
-}
-
 // SSE of the lane's blocks under S = mant_value(MI) * scale2 (scale2 a power of two), entered
-// into the group's arg-min at position POS.  w holds the lane's quotients v / mant_value(MI).
-template <int B, int MI, int POS>
-__device__ __forceinline__ void try_candidate(const float (&v)[8], const float (&w)[8], float scale2,
-                                              GroupBest<B>& g)
+// into the group at position POS.  w holds the lane's quotients v / mant_value(MI).
+template <int B, int MI, int POS, class G>
+__device__ __forceinline__ void try_candidate(const float (&v)[8], const float (&w)[8], float scale2, G& g)
 {
-    constexpr int NBLK = BruteState<B>::NBLK;
     const uint32_t packed = e2m1_pack8(w, scale2);
     float q2[8], sq[8];
     e2m1_unpack8(packed, scale2, q2);                                  // q * 2^e
@@ -78,30 +96,26 @@ __device__ __forceinline__ void try_candidate(const float (&v)[8], const float (
         sq[j] = e * e;
     }
     const float p0 = sq[0] + sq[1], p1 = sq[2] + sq[3], p2 = sq[4] + sq[5], p3 = sq[6] + sq[7];
-    float s[4];
     if constexpr (B == 2) {
-        s[0] = p0; s[1] = p1; s[2] = p2; s[3] = p3;
+        g.template put<POS>(0, p0); g.template put<POS>(1, p1);
+        g.template put<POS>(2, p2); g.template put<POS>(3, p3);
     } else if constexpr (B == 4) {
-        s[0] = p0 + p1; s[1] = p2 + p3;
+        g.template put<POS>(0, p0 + p1); g.template put<POS>(1, p2 + p3);
     } else {
-        s[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
-    }
-#pragma unroll
-    for (int k = 0; k < NBLK; ++k) {
-        const bool better = s[k] < g.sse[k];                           // strict: ties keep the lower code
-        g.sse[k] = better ? s[k] : g.sse[k];
-        g.pos[k] = better ? (uint32_t)POS : g.pos[k];
+        g.template put<POS>(0, group_sum<B / 8>((p0 + p1) + (p2 + p3)));
     }
 }
 
-template <int B, int FMT, int MI>
+template <int B, int FMT, int MI, class G>
 __device__ __forceinline__ void try_binade_from(const float (&v)[8], const float (&w)[8][8], float scale2,
-                                                uint32_t code0, GroupBest<B>& g)
+                                                uint32_t code0, G& g)
 {
-    if constexpr (MI < 8) {
-        if (code0 + MI <= (uint32_t)ScaleFmt<FMT>::kMaxCode)            // skips the NaN code only
-            try_candidate<B, MI, MI>(v, w[MI], scale2, g);
+    if constexpr (MI < 7) {
+        try_candidate<B, MI, MI>(v, w[MI], scale2, g);
         try_binade_from<B, FMT, MI + 1>(v, w, scale2, code0, g);
+    } else {
+        if (code0 + 7u <= (uint32_t)ScaleFmt<FMT>::kMaxCode)            // skips the NaN code only
+            try_candidate<B, 7, 7>(v, w[7], scale2, g);
     }
 }
 
@@ -110,10 +124,10 @@ template <int B, int FMT>
 __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)[8][8], float scale2,
                                            uint32_t code0, BruteState<B>& st)
 {
-    GroupBest<B> g;
-    group_begin<B>(st, g);
+    GroupArgMin<B> g;
+    g.begin();
     try_binade_from<B, FMT, 0>(v, w, scale2, code0, g);
-    group_end<B>(st, g, code0);
+    g.end(st, code0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -221,8 +235,8 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
     const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
     const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
     if (lo_w < 8u) {                                                    // uniform
-        GroupBest<B> g;
-        group_begin<B>(st, g);
+        GroupArgMin<B> g;
+        g.begin();
         try_candidate<B, 0, 0>(v, w[0], s1, g);
         try_candidate<B, 0, 1>(v, w[0], s2, g);
         try_candidate<B, 4, 2>(v, w[4], s2, g);
@@ -230,7 +244,7 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
         try_candidate<B, 2, 4>(v, w[2], s4, g);
         try_candidate<B, 4, 5>(v, w[4], s4, g);
         try_candidate<B, 6, 6>(v, w[6], s4, g);
-        group_end<B>(st, g, 1u);
+        g.end(st, 1u);
     }
 
     // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
