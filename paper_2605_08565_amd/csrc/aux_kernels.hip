@@ -42,10 +42,18 @@ dequant_bf16_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restric
             for (int i = 0; i < count / 2; ++i) packed |= (uint32_t)cb[i] << (8 * i);
         }
         float S[NBLK];
+        if (B < 8 && count == 8) {                  // the lane's 8/B scale bytes in one load
+            uint32_t sb;
+            if constexpr (NBLK == 4) sb = *reinterpret_cast<const uint32_t*>(scales + chunk * 4);
+            else sb = *reinterpret_cast<const uint16_t*>(scales + chunk * 2);
 #pragma unroll
-        for (int k = 0; k < NBLK; ++k) {
-            const int64_t blk = (B >= 8) ? chunk / LANES : chunk * NBLK + k;
-            S[k] = (B >= 8 || k < count / B) ? scale_byte_value(fmt, scales[blk]) : 0.0f;
+            for (int k = 0; k < NBLK; ++k) S[k] = scale_byte_value(fmt, (sb >> (8 * k)) & 0xFFu);
+        } else {
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k) {
+                const int64_t blk = (B >= 8) ? chunk / LANES : chunk * NBLK + k;
+                S[k] = (B >= 8 || k < count / B) ? scale_byte_value(fmt, scales[blk]) : 0.0f;
+            }
         }
         float r[8];
         e2m1_unpack8(packed, 1.0f, r);
@@ -87,10 +95,16 @@ dequant_f32_kernel(const uint16_t* __restrict__ codes, const uint8_t* __restrict
         const uint32_t packed = (count == 4) ? (uint32_t)__builtin_nontemporal_load(codes + h)
                                              : (uint32_t)reinterpret_cast<const uint8_t*>(codes)[h * 2];
         float S[NBLK];
+        if (B == 2 && count == 4) {                 // both scale bytes of the lane in one load
+            const uint32_t sb = *reinterpret_cast<const uint16_t*>(scales + h * 2);
 #pragma unroll
-        for (int k = 0; k < NBLK; ++k) {
-            const int64_t blk = (B >= 4) ? first / B : h * NBLK + k;
-            S[k] = (B >= 4 || k < count / B) ? scale_byte_value(fmt, scales[blk]) : 0.0f;
+            for (int k = 0; k < NBLK; ++k) S[k] = scale_byte_value(fmt, (sb >> (8 * k)) & 0xFFu);
+        } else {
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k) {
+                const int64_t blk = (B >= 4) ? first / B : h * NBLK + k;
+                S[k] = (B >= 4 || k < count / B) ? scale_byte_value(fmt, scales[blk]) : 0.0f;
+            }
         }
         float r[4];
         e2m1_unpack2<0>(packed, 1.0f, r[0], r[1]);

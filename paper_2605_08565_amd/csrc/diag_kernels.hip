@@ -30,11 +30,22 @@ clip_sse_kernel(const void* __restrict__ x, const uint8_t* __restrict__ scales, 
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = v[i] / T;
         }
+        uint32_t sb[NBLK];                          // the lane's scale bytes; one load for a full chunk
+        if (B < 8 && count == 8) {
+            uint32_t w;
+            if constexpr (NBLK == 4) w = *reinterpret_cast<const uint32_t*>(scales + chunk * 4);
+            else w = *reinterpret_cast<const uint16_t*>(scales + chunk * 2);
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k) sb[k] = (w >> (8 * k)) & 0xFFu;
+        } else {
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k)
+                sb[k] = (k * EPB < count) ? (uint32_t)scales[(B >= 8) ? chunk / LANES : chunk * NBLK + k] : 0u;
+        }
         float sq[8];
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) {
-            float S = 0.0f;
-            if (k * EPB < count) S = scale_byte_value(fmt, scales[(B >= 8) ? chunk / LANES : chunk * NBLK + k]);
+            const float S = (k * EPB < count) ? scale_byte_value(fmt, sb[k]) : 0.0f;
             const float lim = 6.0f * S;
 #pragma unroll
             for (int i = 0; i < EPB; ++i) {
@@ -50,13 +61,19 @@ clip_sse_kernel(const void* __restrict__ x, const uint8_t* __restrict__ scales, 
             const float s = group_sum<LANES>((p0 + p1) + (p2 + p3));
             if (count > 0 && (threadIdx.x & (LANES - 1)) == 0) out[chunk / LANES] = s;
         } else if constexpr (B == 4) {
-            if (count >= 4) out[chunk * 2] = p0 + p1;
-            if (count >= 8) out[chunk * 2 + 1] = p2 + p3;
+            if (count == 8) {
+                reinterpret_cast<float2*>(out)[chunk] = make_float2(p0 + p1, p2 + p3);
+            } else if (count >= 4) {
+                out[chunk * 2] = p0 + p1;
+            }
         } else {
-            if (count >= 2) out[chunk * 4] = p0;
-            if (count >= 4) out[chunk * 4 + 1] = p1;
-            if (count >= 6) out[chunk * 4 + 2] = p2;
-            if (count >= 8) out[chunk * 4 + 3] = p3;
+            if (count == 8) {
+                reinterpret_cast<float4*>(out)[chunk] = make_float4(p0, p1, p2, p3);
+            } else {
+                if (count >= 2) out[chunk * 4] = p0;
+                if (count >= 4) out[chunk * 4 + 1] = p1;
+                if (count >= 6) out[chunk * 4 + 2] = p2;
+            }
         }
     }
 }
