@@ -82,6 +82,7 @@ def test_argument_validation_without_a_launch(mxq):
     assert q(scales=P + 2) == mxq.ERR_ALIGNMENT
     assert q(sse=P + 4) == mxq.ERR_ALIGNMENT
     assert q(rows=1 << 40, cols=1 << 40) == mxq.ERR_INVALID_ARG
+    assert q(rows=1 << 30, cols=1 << 12) == mxq.ERR_UNSUPPORTED        # 2^42 elements: beyond the slice counters
     # empty tensors are a valid no-op, also with NULL pointers
     assert q(rows=0) == mxq.OK
     assert q(rows=0, x=None, codes=None, scales=None, sse=None) == mxq.OK
