@@ -104,9 +104,9 @@ __device__ __forceinline__ float tensor_scale_of(float absmax)
 // because v != t*d implies |v/(t*d) - 1| >= 2^-24, which is more than half an ulp of t away.
 // The same holds for  y = fl32(v*r_hi + fl32(v*r_lo))  with r_hi + r_lo = 1/d to 2^-47
 // relative (r_hi need not be the nearest float for that): y is within 2^-46 relative of v/d
-// before its single rounding, far inside the 2^-28 margin the inequality above leaves.  So y may stand in for the IEEE quotient
-// wherever only the rounded code is needed.  (The residual v - q*S is computed from v, q and
-// S, never from y.)
+// before its single rounding, far inside the 2^-28 margin the inequality above leaves.  So y
+// may stand in for the IEEE quotient wherever only the rounded code is needed.  (The residual
+// v - q*S is computed from v, q and S, never from y.)
 // ---------------------------------------------------------------------------------------
 struct Recip { float hi, lo; };
 
@@ -249,10 +249,6 @@ __device__ __forceinline__ float group_sum(float v)
 // ---------------------------------------------------------------------------------------
 // Loads: 8 consecutive elements per lane, widened to fp32.
 // ---------------------------------------------------------------------------------------
-template <int DT> struct Elem;
-template <> struct Elem<kBF16> { using type = uint16_t; };
-template <> struct Elem<kF32> { using type = float; };
-
 template <int DT>
 __device__ __forceinline__ void load8(const void* x, int64_t first, float (&v)[8])
 {
