@@ -141,3 +141,23 @@ def test_binding_fails_loudly_without_the_library(mxq, monkeypatch):
     monkeypatch.setattr(mxq, "LIB_PATH", "/nonexistent/libmxq.so")
     with pytest.raises(ImportError):
         mxq.lib()
+
+
+def test_header_is_plain_c_and_links(tmp_path, mxq):
+    """include/mxq.h compiles as strict C99 and a C program linked against libmxq.so can call the
+    host helpers (no GPU needed)."""
+    import subprocess
+    src = tmp_path / "use_mxq.c"
+    src.write_text('#include "mxq.h"\n'
+                   '#include <stdio.h>\n'
+                   'int main(void) {\n'
+                   '    printf("%d %d %g %s\\n", mxq_num_candidates(MXQ_SCALE_E4M3), mxq_num_candidates(MXQ_SCALE_UE5M3),\n'
+                   '           (double)mxq_scale_decode(MXQ_SCALE_E4M3, 0x7E), mxq_status_string(MXQ_ERR_ALIGNMENT));\n'
+                   '    return 0;\n'
+                   '}\n')
+    exe = tmp_path / "use_mxq"
+    libdir = os.path.dirname(mxq.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lmxq", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()
+    assert out == ["126", "254", "448", "MXQ_ERR_ALIGNMENT"]
