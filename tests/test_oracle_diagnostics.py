@@ -75,3 +75,15 @@ def test_histograms(oracle):
     # independent count of one bin
     nib = np.concatenate([(c & 0xF).ravel(), (c >> 4).ravel()])
     assert oracle.histograms(c, s)[0][3] == int(((nib & 7) == 3).sum())
+
+
+def test_histograms_hand_counted(oracle):
+    """Explicit bytes, counts written out by hand: both nibbles of a byte are counted, the sign
+    bit (bit 3 of a nibble) is ignored, scale bytes are counted as they are."""
+    codes = np.array([[0x10, 0x92, 0x7F]], np.uint8)      # nibbles 0,1 | 2,9 | 15,7 -> magnitudes 0,1,2,1,7,7
+    scales = np.array([[3, 3, 200]], np.uint8)
+    eh, sh = oracle.histograms(codes, scales)
+    assert list(eh) == [1, 2, 1, 0, 0, 0, 0, 2]
+    want = np.zeros(256, np.uint64)
+    want[3], want[200] = 2, 1
+    assert (sh == want).all()
