@@ -256,6 +256,27 @@ def test_randomised_wide_dynamic_range(oracle, mxq):
                 check(oracle, mxq, data, block, fmt, rec, T=T if fmt else 1.0, tag=f"random-{case}")
 
 
+def test_nan_and_inf_stay_inside_their_blocks(oracle, mxq):
+    """NaN / Inf elements give unspecified results for their own block only (every table index
+    and loop bound in the kernels is clamped, so nothing can fault): all other blocks equal the
+    oracle's.  Rows 1, 3 and 5 carry the special values; blocks never straddle rows."""
+    x = W.normal_f32(8, 256, seed=12, sigma=0.05)
+    x[1, 7] = np.nan
+    x[3, 100] = np.inf
+    x[5, 31] = -np.inf
+    x[5, 200] = np.nan
+    clean = [0, 2, 4, 6, 7]
+    for data in (x, W.f32_to_bf16_bits(x)):
+        for block in (2, 16, 128):
+            for fmt, rec in combos():
+                print(f"[parity] specials dtype={data.dtype} b={block} fmt={FMT_NAMES[fmt]} recipe={REC_NAMES[rec]}",
+                      flush=True)
+                gc, gs, ge = run_gpu(mxq, data, block, fmt, rec)
+                oc, os_, oe = oracle.quantize(np.ascontiguousarray(data[clean]), block, fmt, ORACLE_REC[rec])
+                assert (gc[clean] == oc).all() and (gs[clean] == os_).all()
+                assert (ge[clean].view(np.uint32) == oe.view(np.uint32)).all()
+
+
 def test_sse_out_may_be_null(oracle, mxq):
     x_np = W.student_t_weights(16, 256, seed=5)
     x = mxq.from_bits(x_np)
