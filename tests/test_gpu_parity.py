@@ -419,26 +419,29 @@ def test_config3_full_size(oracle, mxq):
             check_full(oracle, x_np, out, block, 1, rec, T=T)
 
 
-def test_config4_brute_full_size_sampled(oracle, mxq):
-    """Brute-force search on the full 4096 x 14336 weights; the oracle checks 256 whole rows (1/16 of the tensor) per
-    run; brute-force SSE <= 4-over-6 SSE <= abs-max SSE on every block."""
+@pytest.mark.parametrize("fmt,block", [(1, 16), (1, 4), (2, 16), (2, 4)])
+def test_config4_brute_full_size(oracle, mxq, fmt, block):
+    """Brute-force search (126 / 254 candidates) on the full 4096 x 14336 weights, compared with
+    the oracle on the WHOLE tensor (in chunks of 512 rows); brute-force SSE <= 4-over-6 SSE <=
+    abs-max SSE on every block; the pruned search returns the same bytes."""
     x_np = W.config2()
     x = mxq.from_bits(x_np)
-    rows = sample_rows(x_np.shape[0], 256, seed=4)
-    for block in (4, 16):
+    out = mxq.quantize(x, block, fmt, 4)
+    torch.cuda.synchronize()
+    gc, gs, ge = (t.cpu().numpy() for t in out)
+    for r0 in range(0, x_np.shape[0], 512):
+        print(f"[parity] config4 b={block} fmt={FMT_NAMES[fmt]} brute rows {r0}..{r0 + 511}", flush=True)
+        sl = slice(r0, r0 + 512)
+        oc, os_, oe = oracle.quantize(np.ascontiguousarray(x_np[sl]), block, fmt, 4)
+        assert (gs[sl] == os_).all() and (gc[sl] == oc).all()
+        assert (ge[sl].view(np.uint32) == oe.view(np.uint32)).all()
+    if fmt == 1:
         ab = mxq.quantize(x, block, 1, 0)[2]
         f6 = mxq.quantize(x, block, 1, 2)[2]
-        for fmt in (1, 2):
-            print(f"[parity] config4 b={block} fmt={FMT_NAMES[fmt]} brute", flush=True)
-            out = mxq.quantize(x, block, fmt, 4)
-            torch.cuda.synchronize()
-            check_rows(oracle, x_np, rows, out, block, fmt, 4)
-            if fmt == 1:
-                assert bool((out[2] <= f6).all()) and bool((f6 <= ab).all())
-            # the pruned search returns the same bytes as the full enumeration on the whole tensor
-            pr = mxq.quantize(x, block, fmt, 5)
-            torch.cuda.synchronize()
-            assert all(torch.equal(a, b) for a, b in zip(out, pr))
+        assert bool((out[2] <= f6).all()) and bool((f6 <= ab).all())
+    pr = mxq.quantize(x, block, fmt, 5)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(out, pr))
 
 
 def test_config5_layer0(oracle, mxq):
