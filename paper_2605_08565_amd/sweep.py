@@ -9,9 +9,12 @@ UE5M3 abs-max, E4M3 brute force; block sizes 2 ... 128.  For every (recipe, bloc
 seven matrices of a layer are quantised back to back (436 MB of input between two touches of
 a matrix, so the 256 MB Infinity Cache does not help), as one HIP graph replay with one event
 pair around it.
-Reports GElem/s and the aggregate MSE per (recipe, block size).  Weights are drawn on the GPU
-(this driver measures throughput and quality trends; bit-parity with the CPU oracle is the
-job of the tests, which use the numpy generator of ``workloads``).
+Reports GElem/s and the aggregate MSE per (recipe, block size).
+
+Weights come from ``workloads.layer_matrix`` (numpy Philox, drawn on the host one layer ahead of
+the GPU and uploaded): the same bytes the parity tests feed to the CPU oracle.  ``--generator
+gpu`` draws them with torch's generator on the device instead (faster start-up, same
+distribution, but bytes no test compares); the output says which generator produced the figures.
 """
 from __future__ import annotations
 
@@ -19,11 +22,28 @@ import argparse
 import json
 import sys
 
-from .workloads import LAYER_SHAPES, N_LAYERS
+from concurrent.futures import ThreadPoolExecutor
+
+from .workloads import LAYER_SHAPES, N_LAYERS, layer_matrix
 
 RECIPES = [("pow2_mx", 0, 0), ("e4m3_absmax", 1, 0), ("e4m3_prevent_zero", 1, 1),
            ("e4m3_4over6", 1, 2), ("ue5m3_absmax", 2, 0), ("e4m3_brute", 1, 4)]
 BLOCKS = (2, 4, 8, 16, 32, 64, 128)
+
+
+def host_layer(layer: int) -> dict:
+    """The seven matrices of layer `layer` as bf16 bit patterns (numpy uint16), from
+    ``workloads.layer_matrix``; the matrices are drawn by parallel threads."""
+    names = list(LAYER_SHAPES)
+    with ThreadPoolExecutor(max_workers=len(names)) as pool:
+        return dict(zip(names, pool.map(lambda n: layer_matrix(layer, n), names)))
+
+
+def upload_layer(host: dict, mats) -> None:
+    """Copy a host layer into the seven resident weight buffers."""
+    import torch
+    for name, x in mats.items():
+        x.view(torch.int16).copy_(torch.from_numpy(host[name].view("int16")))
 
 
 def draw_layer(layer: int, mats) -> None:
@@ -40,7 +60,8 @@ def draw_layer(layer: int, mats) -> None:
         x.copy_(0.02 * z / torch.sqrt(chi / 4.0))
 
 
-def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool = True) -> dict:
+def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool = True,
+        generator: str = "numpy", layer_ids=None) -> dict:
     """The smallest matrices (k, v: 4 M elements) quantise in a few microseconds, less than one
     launch through Python costs, so the seven launches of a (recipe, block size) group are
     captured once into a HIP graph over resident buffers and replayed for every layer."""
@@ -82,8 +103,17 @@ def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool
                 graphs[(rn, b)] = g
         torch.cuda.synchronize()
 
-    for layer in range(layers):
-        draw_layer(layer, mats)
+    ids = list(range(layers)) if layer_ids is None else list(layer_ids)
+    ahead = ThreadPoolExecutor(max_workers=1)            # the next layer is drawn while this one runs
+    pending = ahead.submit(host_layer, ids[0]) if (generator == "numpy" and ids) else None
+    for pos, layer in enumerate(ids):
+        if generator == "numpy":
+            host = pending.result()
+            pending = ahead.submit(host_layer, ids[pos + 1]) if pos + 1 < len(ids) else None
+            upload_layer(host, mats)
+            del host
+        else:
+            draw_layer(layer, mats)
         torch.cuda.synchronize()
         for rn, fmt, rec in recipes:
             for b in blocks:
@@ -104,7 +134,9 @@ def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool
     for (rn, b), a in acc.items():
         rows.append({"recipe": rn, "block": b, "gelem_s": round(a["elements"] / a["ms"] / 1e6, 1),
                      "mse": a["sse"] / a["elements"], "elements": a["elements"], "ms": round(a["ms"], 3)})
-    return {"layers": layers, "graphs": use_graphs, "rows": rows}
+    ahead.shutdown()
+    return {"layers": len(ids), "layer_ids": ids, "graphs": use_graphs, "generator": generator,
+            "parity_checked_bytes": generator == "numpy", "rows": rows}
 
 
 def main() -> None:
@@ -112,8 +144,10 @@ def main() -> None:
     ap.add_argument("--layers", type=int, default=N_LAYERS)
     ap.add_argument("--out", default="")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from Python instead")
+    ap.add_argument("--generator", choices=("numpy", "gpu"), default="numpy",
+                    help="numpy: workloads.layer_matrix bytes (the parity-checked ones); gpu: torch draws on the device")
     args = ap.parse_args()
-    res = run(args.layers, use_graphs=not args.no_graphs)
+    res = run(args.layers, use_graphs=not args.no_graphs, generator=args.generator)
     text = json.dumps(res)
     if args.out:
         with open(args.out, "w") as f:

@@ -15,6 +15,8 @@ FMT_NAMES = {0: "e8m0", 1: "e4m3", 2: "ue5m3"}
 REC_NAMES = {0: "absmax", 1: "absmax_pz", 2: "4over6", 3: "4over6_pz", 4: "brute", 5: "brute_pruned"}
 ORACLE_REC = {0: 0, 1: 1, 2: 2, 3: 3, 4: 4, 5: 4}      # the pruned search must equal the full one
 BLOCKS = (2, 4, 8, 16, 32, 64, 128)
+# pow2 MX, E4M3 abs-max, clamp, 4-over-6, UE5M3 abs-max, E4M3 brute force
+CONFIG5_RECIPES = [(0, 0), (1, 0), (1, 1), (1, 2), (2, 0), (1, 4)]
 
 
 @pytest.fixture(scope="module")
@@ -447,13 +449,13 @@ def test_config4_brute_full_size(oracle, mxq, fmt, block):
 def test_config5_layer0(oracle, mxq):
     """Layer 0 of the synthetic 32-layer model, every matrix, every recipe and block size.  The
     streaming recipes are compared on the whole k and v matrices (1024 x 4096) and on 512 whole
-    rows of the larger ones; the brute-force search on 128 whole rows per matrix."""
+    rows of the larger ones; the brute-force search on 129 whole rows per matrix."""
     for name in W.LAYER_SHAPES:
         x_np = W.layer_matrix(0, name)
         x = mxq.from_bits(x_np)
         rows = sample_rows(x_np.shape[0], 512, seed=5)
         for block in BLOCKS:
-            for fmt, rec in [(0, 0), (1, 0), (1, 1), (1, 2), (2, 0), (1, 4)]:
+            for fmt, rec in CONFIG5_RECIPES:
                 print(f"[parity] config5 {name} b={block} fmt={FMT_NAMES[fmt]} "
                       f"recipe={REC_NAMES[rec]}", flush=True)
                 out = mxq.quantize(x, block, fmt, rec)
@@ -464,6 +466,90 @@ def test_config5_layer0(oracle, mxq):
                     check_full(oracle, x_np, out, block, fmt, rec)
                 else:
                     check_rows(oracle, x_np, rows, out, block, fmt, rec)
+
+
+@pytest.mark.parametrize("layer", (1, 15, 31))
+def test_config5_later_layers(oracle, mxq, layer):
+    """Layers beyond the first: the GPU quantises every whole matrix of the layer (the bytes
+    `workloads.layer_matrix` draws, which are also what the sweep driver quantises) with all six
+    recipes at all seven block sizes; 16 seeded whole rows per matrix -- first and last row
+    included, so every block size sees whole blocks -- are compared with the oracle bit for bit."""
+    from paper_2605_08565_amd import sweep
+    layer_np = sweep.host_layer(layer)
+    for name, x_np in layer_np.items():
+        x = mxq.from_bits(x_np)
+        rows = sample_rows(x_np.shape[0], 16, seed=1000 * layer + len(name))
+        for block in BLOCKS:
+            for fmt, rec in CONFIG5_RECIPES:
+                print(f"[parity] config5 layer={layer} {name} b={block} fmt={FMT_NAMES[fmt]} "
+                      f"recipe={REC_NAMES[rec]}", flush=True)
+                out = mxq.quantize(x, block, fmt, rec)
+                torch.cuda.synchronize()
+                check_rows(oracle, x_np, rows, out, block, fmt, rec)
+
+
+# ------------------------------------------------------------------ fp32 input beyond one tile per workgroup
+
+def test_f32_input_grid_stride_ragged(oracle, mxq):
+    """fp32 input whose 5 147 slices of 256 chunks exceed the 2 048 workgroups of the launch, so
+    every workgroup runs the double-buffered loop (and its wavefront-private LDS re-formation)
+    two or three times, with a ragged last slice; the whole tensor against the oracle."""
+    x_np = W.normal_f32(2563, 4112, seed=1101)
+    x_np[5] *= np.float32(1e-3)
+    x_np[100] *= np.float32(40.0)
+    x_np[2000, ::7] = 0.0
+    assert (x_np.size // 8) % 256 != 0 and x_np.size // 8 > 2 * 2048 * 256
+    x = mxq.from_bits(x_np)
+    A = float(mxq.tensor_absmax(x).cpu()[0])
+    assert A == oracle.tensor_absmax(x_np)
+    T = mxq.tensor_scale_from_absmax(A, 1)
+    slow_T = float(np.float32(1.99999988) * np.float32(2.0 ** -7))       # plain-division kernel
+    for block, fmt, rec, t in [(16, 1, 0, 1.0), (16, 1, 2, 1.0), (16, 1, 0, T), (16, 1, 3, T), (8, 1, 2, slow_T),
+                               (16, 0, 0, 1.0), (8, 2, 2, 1.0), (4, 1, 1, 1.0), (2, 1, 2, 1.0), (2, 2, 0, T)]:
+        print(f"[parity] f32-grid-stride b={block} fmt={FMT_NAMES[fmt]} recipe={REC_NAMES[rec]} T={t}", flush=True)
+        out = mxq.quantize(x, block, fmt, rec, tensor_scale=t)
+        torch.cuda.synchronize()
+        check_full(oracle, x_np, out, block, fmt, rec, T=t)
+    # the same tensor through mxq_quantize_hier (T taken from device memory inside the kernel)
+    out = mxq.quantize_hier(x, 16, 1, 2, mxq.tensor_absmax(x))
+    torch.cuda.synchronize()
+    check_full(oracle, x_np, out[:3], 16, 1, 2, T=T)
+    rows = sample_rows(x_np.shape[0], 257, seed=11)
+    for block, fmt, rec, t in [(16, 1, 4, 1.0), (4, 2, 4, 1.0), (8, 1, 5, T)]:
+        print(f"[parity] f32-grid-stride brute b={block} fmt={FMT_NAMES[fmt]} recipe={REC_NAMES[rec]} T={t}", flush=True)
+        out = mxq.quantize(x, block, fmt, rec, tensor_scale=t)
+        torch.cuda.synchronize()
+        check_rows(oracle, x_np, rows, out, block, fmt, rec, T=t)
+
+
+def test_f32_activations_full_size(oracle, mxq):
+    """The 8192 x 4096 activation tensor widened to fp32 (33.5 M elements, 16 384 slices: eight
+    tiles per workgroup): abs-max, 4-over-6, hierarchical abs-max and 4-over-6, power-of-two scales
+    and the widest blocks on the WHOLE tensor; the brute-force search on 512 whole rows."""
+    x_np = W.bf16_bits_to_f32(W.config3())
+    x = mxq.from_bits(x_np)
+    A = float(mxq.tensor_absmax(x).cpu()[0])
+    assert A == oracle.tensor_absmax(x_np)
+    T = mxq.tensor_scale_from_absmax(A, 1)
+    for block, fmt, rec, t in [(16, 1, 0, 1.0), (16, 1, 2, 1.0), (16, 1, 0, T), (32, 1, 2, T), (32, 0, 0, 1.0),
+                               (128, 1, 2, 1.0), (64, 2, 1, 1.0)]:
+        print(f"[parity] f32-activations b={block} fmt={FMT_NAMES[fmt]} recipe={REC_NAMES[rec]} T={t}", flush=True)
+        out = mxq.quantize(x, block, fmt, rec, tensor_scale=t)
+        torch.cuda.synchronize()
+        check_full(oracle, x_np, out, block, fmt, rec, T=t)
+    rows = sample_rows(x_np.shape[0], 512, seed=12)
+    for block, fmt, rec, t in [(16, 1, 4, 1.0), (32, 1, 4, T)]:
+        print(f"[parity] f32-activations brute b={block} T={t}", flush=True)
+        out = mxq.quantize(x, block, fmt, rec, tensor_scale=t)
+        torch.cuda.synchronize()
+        check_rows(oracle, x_np, rows, out, block, fmt, rec, T=t)
+    # de-quantise to fp32 and bf16 at this size (several passes of the grid-stride loops)
+    c, s, _ = mxq.quantize(x, 16, 1, 0, tensor_scale=T)
+    oc, os_, _ = oracle.quantize(x_np, 16, 1, 0, tensor_scale=T)
+    got = mxq.dequantize(c, s, 16, 1, T, torch.float32).cpu().numpy()
+    assert (got.view(np.uint32) == oracle.dequantize(oc, os_, 16, 1, T, oracle.DT_F32).view(np.uint32)).all()
+    got = mxq.dequantize(c, s, 16, 1, T, torch.bfloat16).cpu().view(torch.int16).numpy().view(np.uint16)
+    assert (got == oracle.dequantize(oc, os_, 16, 1, T, oracle.DT_BF16)).all()
 
 
 # ------------------------------------------------------------------ appendix diagnostics

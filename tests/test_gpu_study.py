@@ -29,6 +29,29 @@ def test_study_parity_slice(oracle):
             assert (e.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
 
 
+def test_study_full_size_sigma_columns(oracle):
+    """The complete b = 32 study tensor (151 x 50 000 blocks of fp32, 241.6 M elements, the shape
+    `study.run` launches: every workgroup of the fp32 streaming kernel walks about 58 tiles).  Five
+    whole sigma columns (8 M elements) of abs-max and prevent-zero + 4-over-6, and 4 000 blocks of
+    three columns of the brute-force search, are compared with the oracle bit for bit."""
+    from paper_2605_08565_amd import mxq, study
+    b, per = 32, 50000
+    sig = study.study_sigmas(151)
+    x = study.study_tensor(sig, per, b)
+    xt = mxq.from_bits(x)
+    cols = [0, 1, 75, 149, 150]
+    for name, n_rows in (("absmax", per), ("prevent_zero_4over6", per), ("brute_force", 4000)):
+        rec = study.RECIPES[name]
+        print(f"[study-full] b={b} recipe={name}", flush=True)
+        c, s, e = mxq.quantize(xt, b, 1, rec)
+        torch.cuda.synchronize()
+        for i in (cols if n_rows == per else cols[::2]):
+            sl = slice(i * per, i * per + n_rows)
+            oc, os_, oe = oracle.quantize(x[sl], b, 1, rec)
+            assert (c[sl].cpu().numpy() == oc).all() and (s[sl].cpu().numpy() == os_).all(), (name, i)
+            assert (e[sl].cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all(), (name, i)
+
+
 def test_study_regions(result):
     sig = np.array(result["sigma"])
     m = {r: {int(b): np.array(v) / sig ** 2 for b, v in d.items()} for r, d in result["mse"].items()}
