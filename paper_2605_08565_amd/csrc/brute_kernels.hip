@@ -165,7 +165,7 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t& lo_w
 #pragma unroll
         for (int i = 0; i < EPB; ++i) a = fmaxf(a, __builtin_fabsf(v[k * EPB + i]));
         amax[k] = group_max<LANES>(a);
-        cref[k] = max(sf_encode_rne<FMT>(__builtin_fmaf(amax[k], kSixthHi, amax[k] * kSixthLo)), 1u);
+        cref[k] = max(sf_encode_rne<FMT>(sixth_of(amax[k])), 1u);
         S[k] = sf_decode<FMT>(cref[k]);
         const Recip r = make_recip(S[k]);
 #pragma unroll

@@ -1,6 +1,7 @@
 // C ABI of libmxq (see include/mxq.h): host-side validation and dispatch.  No allocation, no
 // synchronisation, no global state.
 #include "../../include/mxq.h"
+#include "mxq_arith.hpp"
 #include "mxq_launch.hpp"
 
 #include <cmath>
@@ -189,10 +190,7 @@ float mxq_tensor_scale_from_absmax(float absmax, int elem_fmt, int scale_fmt)
     else if (scale_fmt == MXQ_SCALE_E4M3) sf_max = 448.0f;
     else if (scale_fmt == MXQ_SCALE_UE5M3) sf_max = 114688.0f;
     else return NAN;
-    if (!(absmax > 0.0f)) return 1.0f;
-    const float denom = 6.0f * sf_max;
-    const float t = absmax / denom;
-    return (t > 0.0f && !std::isinf(t)) ? t : 1.0f;
+    return mxq::tensor_scale_from(absmax, sf_max);      // the function the kernels call
 }
 
 float mxq_scale_decode(int scale_fmt, uint8_t code) { return host_scale_decode(scale_fmt, code); }

@@ -7,13 +7,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mxq_arith.hpp"      // the division-free sequences, shared with the host-side proof
+
 namespace mxq {
 
 constexpr int kE8M0 = 0, kE4M3 = 1, kUE5M3 = 2;
 constexpr int kBF16 = 0, kF32 = 1;
-
-__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
-__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
 
 // ---------------------------------------------------------------------------------------
 // 8-bit floating-point scale formats (Background; eps under Eq. 3).
@@ -30,39 +29,22 @@ template <> struct ScaleFmt<kUE5M3> {
     static constexpr float kMaxValue = 114688.0f;
 };
 
-// Value of a finite scale code: m * 2^(1-bias-3) below the first binade, else
-// (1 + m/8) * 2^(e-bias), built directly as fp32 bits.
 template <int FMT>
-__device__ __forceinline__ float sf_decode(uint32_t code)
-{
-    constexpr int bias = ScaleFmt<FMT>::kBias;
-    const float sub = (float)(code & 7u) * u2f((uint32_t)(127 + 1 - bias - 3) << 23);
-    const float nrm = u2f((code + ((127u - bias) << 3)) << 20);
-    return (code < 8u) ? sub : nrm;
-}
+__device__ __forceinline__ float sf_decode(uint32_t code) { return sf_decode_bias<ScaleFmt<FMT>::kBias>(code); }
 
 // Round_SF of Eq. 2: round-to-nearest-even of y >= 0 into the format, clipped to the largest
-// finite value.  Normal range: RNE of the fp32 mantissa to 3 bits by the usual
-// add-half-minus-one-plus-lsb on the bit pattern.  Sub-normal range: adding 2^(emin+20)
-// makes the fp32 adder itself round y to a multiple of eps (ties to even).
-//
-// For E4M3 the gfx950 conversion v_cvt_pk_fp8_f32 does the same rounding (OCP E4M3, nearest
-// even, sub-normals included) in one instruction; it turns values beyond 448 into NaN rather
-// than clipping, hence the clamp in front of it.
+// finite value.  For E4M3 the gfx950 conversion v_cvt_pk_fp8_f32 does the rounding (OCP E4M3,
+// nearest even, sub-normals included) in one instruction; it turns values beyond 448 into NaN
+// rather than clipping, hence the clamp in front of it.  UE5M3 rounds on the bit pattern.
 template <int FMT>
 __device__ __forceinline__ uint32_t sf_encode_rne(float y)
 {
-    constexpr int bias = ScaleFmt<FMT>::kBias;
     y = fminf(y, ScaleFmt<FMT>::kMaxValue);
     if constexpr (FMT == kE4M3) {
         return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(y, y, 0, false) & 0xFFu;
+    } else {
+        return sf_encode_bits<ScaleFmt<FMT>::kBias>(y);
     }
-    const uint32_t b = f2u(y);
-    const uint32_t nrm = ((b + 0x7FFFFu + ((b >> 20) & 1u)) >> 20) - ((127u - bias) << 3);
-    const float magic = u2f((uint32_t)(127 + (1 - bias) + 20) << 23);
-    const uint32_t sub = f2u(y + magic) - f2u(magic);
-    const float min_normal = u2f((uint32_t)(127 + 1 - bias) << 23);
-    return (y < min_normal) ? sub : nrm;
 }
 
 // Value of any scale byte of any format (NaN for bytes that are not finite numbers); used where
@@ -78,54 +60,15 @@ __device__ __forceinline__ float scale_byte_value(int fmt, uint32_t code)
     return (code > (uint32_t)ScaleFmt<kUE5M3>::kMaxCode) ? nan : sf_decode<kUE5M3>(code);
 }
 
-// Per-tensor scale of hierarchical scaling (Section 2, two-stage process) from the tensor
-// abs-max: the abs-max lands on (largest element magnitude) x (largest scale value).  The same
-// float operations as the host helper of the C ABI, so both give the same bits; 1 for an
-// all-zero tensor or when the quotient vanishes (6 * 2^127 overflows for power-of-two scales).
+// Per-tensor scale of hierarchical scaling from the tensor abs-max: the same function as the
+// host helper of the C ABI, so both give the same bits.
 template <int FMT>
 __device__ __forceinline__ float tensor_scale_of(float absmax)
 {
     float sf_max;
     if constexpr (FMT == kE8M0) sf_max = u2f(254u << 23);
     else sf_max = ScaleFmt<FMT>::kMaxValue;
-    if (!(absmax > 0.0f)) return 1.0f;
-    const float t = absmax / (6.0f * sf_max);
-    return (t > 0.0f && t < __builtin_inff()) ? t : 1.0f;
-}
-
-// ---------------------------------------------------------------------------------------
-// Quotients whose rounding decisions are exact.
-//
-// The method divides in IEEE fp32 (v / S, amax / M) and then rounds the quotient to a very
-// coarse grid (E2M1, or an 8-bit scale format).  Only the side of each grid mid-point t the
-// quotient falls on matters.  For a divisor d with at most 4 significant bits and a
-// mid-point t with at most 5, the product t*d is exact in fp32, and for fp32 v
-//     fl32(v / d) <, =, > t   <=>   v <, =, > t*d,
-// because v != t*d implies |v/(t*d) - 1| >= 2^-24, which is more than half an ulp of t away.
-// The same holds for  y = fl32(v*r_hi + fl32(v*r_lo))  with r_hi + r_lo = 1/d to 2^-47
-// relative (r_hi need not be the nearest float for that): y is within 2^-46 relative of v/d
-// before its single rounding, far inside the 2^-28 margin the inequality above leaves.  So y
-// may stand in for the IEEE quotient wherever only the rounded code is needed.  (The residual
-// v - q*S is computed from v, q and S, never from y.)
-// ---------------------------------------------------------------------------------------
-struct Recip { float hi, lo; };
-
-// r_hi = 1/d rounded toward zero, r_lo = fl32(rho * r_hi) >= 0 with rho = 1 - r_hi*d exact (fma).
-// Both parts are non-negative, so both products in quot() carry the sign of v and a zero
-// quotient (v = -0, or an underflowing product) keeps the sign bit of v.
-__device__ __forceinline__ Recip make_recip(float d)
-{
-    Recip r;
-    r.hi = 1.0f / d;
-    if (__builtin_fmaf(-r.hi, d, 1.0f) < 0.0f) r.hi = u2f(f2u(r.hi) - 1u);      // was rounded up
-    const float rho = __builtin_fmaf(-r.hi, d, 1.0f);
-    r.lo = rho * r.hi;
-    return r;
-}
-
-__device__ __forceinline__ float quot(float v, Recip r)
-{
-    return __builtin_fmaf(v, r.hi, v * r.lo);
+    return tensor_scale_from(absmax, sf_max);
 }
 
 // (scale value, reciprocal hi/lo) for every scale byte, filled once per workgroup into LDS.
@@ -146,9 +89,6 @@ __device__ __forceinline__ void fill_scale_table(ScaleEntry* tab)
     }
     __syncthreads();
 }
-
-constexpr float kSixthHi = (float)(1.0 / 6.0);
-constexpr float kSixthLo = (float)(1.0 / 6.0 - (double)kSixthHi);
 
 // ---------------------------------------------------------------------------------------
 // E2M1 (Section 2 value set {0, .5, 1, 1.5, 2, 3, 4, 6}).

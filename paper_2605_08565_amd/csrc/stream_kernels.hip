@@ -22,8 +22,8 @@ namespace mxq {
 template <int FMT, bool FOUR6>
 __device__ __forceinline__ void absmax_codes(float amax, uint32_t floor_code, uint32_t& c6, uint32_t& c4)
 {
-    const float y6 = __builtin_fmaf(amax, kSixthHi, amax * kSixthLo);
-    const float y4 = amax * 0.25f;
+    const float y6 = sixth_of(amax);
+    const float y4 = quarter_of(amax);
     if constexpr (FMT == kE4M3) {
         const float m = ScaleFmt<kE4M3>::kMaxValue;
         const uint32_t both = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(y6, m), fminf(y4, m), 0, false);
@@ -33,15 +33,6 @@ __device__ __forceinline__ void absmax_codes(float amax, uint32_t floor_code, ui
         c6 = max(sf_encode_rne<FMT>(y6), floor_code);
         c4 = FOUR6 ? max(sf_encode_rne<FMT>(y4), floor_code) : 0u;
     }
-}
-
-// Eq. 1: k = floor(log2(amax / 6)).  With amax = m * 2^e, 1 <= m < 2: k = e - 2 when
-// m >= 1.5, else e - 3; byte = k + 127, never below 0 (sub-normal or zero amax gives 0).
-__device__ __forceinline__ uint32_t pow2_code(float amax)
-{
-    const uint32_t b = f2u(amax);
-    const int c = (int)(b >> 23) - 3 + (int)((b >> 22) & 1u);
-    return (uint32_t)max(c, 0);
 }
 
 // Quantise the lane's 8 values (NBLK blocks of EPB elements, one scale code each) under
@@ -127,32 +118,11 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
     }
 }
 
-// Hierarchical scaling divides every input by the per-tensor scale T in IEEE fp32.  T is the
-// same for the whole tensor, so its correctly rounded reciprocal r is formed once and each
-// quotient is refined once:
-//     q0 = v*r;  q1 = q0 - r*(q0*T - v)                                 (remainder by FMA)
-// q0 is within 1.5 ulp of v/T and the value rounded into q1 differs from the exact quotient by
-// less than 3 * 2^-24 ulp, so q1 is the correctly rounded quotient unless v/T lies that close
-// to the midpoint of two floats; all mantissa pairs that come so close (an integer congruence
-// lists them) are checked one by one on the host, the all-ones mantissa of T excluded.  The
-// remainder is formed with the opposite sign (q0*T - v) and subtracted, which keeps a signed
-// zero: for v = -0 the last step is (-0)*r + (-0) = -0, whereas v - q0*T would give +0 and
-// lose the sign.  The argument needs intermediate results free of
-// overflow and underflow: the host takes this path only for 2^-20 <= T <= 2^20 with a
-// mantissa that is not all ones, and a block whose adjusted abs-max leaves [2^-40, 2^90]
-// (zero excepted) sends its whole wavefront through the plain division instead.  An element far
-// below its block's abs-max can still have |v/T| < 2^-78, where the remainder may underflow and
-// q1 be off by one ulp; nothing observes that: the element quantises to a signed zero and its
-// squared residual underflows to zero either way.
+// Division by the per-tensor scale T of hierarchical scaling: div_by_T (reciprocal + one FMA
+// refinement, exact inside the range fast_division_ok / fast_division_unsafe_amax delimit) or the
+// plain IEEE division.
 enum : int { kNoT = 0, kFastT = 1, kSlowT = 2, kDynT = 3 };   // kDynT: T comes from device memory, one of
                                                               // the other three is chosen at run time
-
-__device__ __forceinline__ float div_by_T(float v, float T, float rT)
-{
-    const float q0 = v * rT;
-    const float neg_rem = __builtin_fmaf(q0, T, -v);                 // q0*T - v, exact
-    return __builtin_fmaf(-neg_rem, rT, q0);
-}
 
 template <int NBLK, int EPB, int LANES>
 __device__ __forceinline__ void block_amax(const float (&v)[8], float (&amax)[NBLK])
@@ -183,7 +153,7 @@ __device__ __forceinline__ void adjust_and_amax(float (&v)[8], float T, float rT
         bool unsafe = false;
 #pragma unroll
         for (int k = 0; k < NBLK; ++k)                  // 0 < amax < 2^-40  or  amax > 2^90
-            unsafe |= (f2u(amax[k]) - 0x2B800000u) > (0x6C800000u - 0x2B800000u) && f2u(amax[k]) != 0u;
+            unsafe |= fast_division_unsafe_amax(amax[k]);
         if (__builtin_amdgcn_ballot_w64(unsafe) != 0ull) {       // rare, wave-uniform
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = raw[i] / T;
@@ -192,14 +162,6 @@ __device__ __forceinline__ void adjust_and_amax(float (&v)[8], float T, float rT
     } else {
         block_amax<NBLK, EPB, LANES>(v, amax);
     }
-}
-
-// The reciprocal-refined division is exact for these T only (see div_by_T).
-__host__ __device__ inline bool fast_division_ok(float T)
-{
-    uint32_t tb;
-    __builtin_memcpy(&tb, &T, 4);
-    return T >= 0x1p-20f && T <= 0x1p20f && (tb & 0x7FFFFFu) != 0x7FFFFFu;
 }
 
 // Everything between the load and the store for one lane's 8 values.  `tdyn` (one of kNoT,

@@ -1,32 +1,23 @@
 /*
- * CPU emulation of the arithmetic shortcuts the HIP kernels take, checked against the plain
- * definitions over (near-)exhaustive input sets.  This file shares nothing with the oracle:
- * it re-states, with fmaf on the host, the exact instruction sequences of
- * paper_2605_08565_amd/csrc (make_recip / quot, the scale encode of amax/6 and amax/4, the
- * power-of-two code of Eq. 1, the reciprocal-refined division by the per-tensor scale) and
- * compares every DECISION they lead to with exact arithmetic in double precision.
+ * The arithmetic shortcuts of the HIP kernels, run on the CPU against the plain definitions over
+ * (near-)exhaustive input sets.  The sequences under test are NOT re-typed here: this program
+ * includes paper_2605_08565_amd/csrc/mxq_arith.hpp, the very header the kernels are built from
+ * (make_recip / quot, sixth_of / quarter_of and the scale encode, pow2_code, div_by_T
+ * with its range predicates, sf_decode_bias), and compares every DECISION they lead to with
+ * exact arithmetic in double precision.  It shares nothing with the oracle.
  *
  * Prints one line per check: "<name> cases=<n> bad=<m>"; exit status 0 iff all bad == 0.
- * Build: gcc -O2 -ffp-contract=off -mfma -fopenmp.
+ * Build: g++ -O2 -std=c++17 -ffp-contract=off -mfma -fopenmp.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
 
-static inline float u2f(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
-static inline uint32_t f2u(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+#include "../../paper_2605_08565_amd/csrc/mxq_arith.hpp"
 
-/* the kernel's reciprocal split: r_hi = 1/d rounded toward zero, r_lo = fl(rho * r_hi) */
-static void make_recip(float d, float* hi, float* lo)
-{
-    volatile float r = 1.0f / d;
-    if (fmaf(-r, d, 1.0f) < 0.0f) r = u2f(f2u(r) - 1u);
-    float rho = fmaf(-r, d, 1.0f);
-    *hi = r;
-    *lo = rho * r;
-}
-static inline float quot(float v, float hi, float lo) { volatile float p = v * lo; return fmaf(v, hi, p); }
+using mxq::f2u;
+using mxq::u2f;
 
 /* E2M1 magnitude index by the conversion instruction's rule (RNE, saturate) */
 static int e2m1_index(double ay)
@@ -50,13 +41,12 @@ static long check_quot(long* cases)
     long bad = 0, n = 0;
     for (int mi = 0; mi < 8; ++mi) {
         const float S = 1.0f + mi * 0.125f;
-        float hi, lo;
-        make_recip(S, &hi, &lo);
+        const mxq::Recip r = mxq::make_recip(S);
 #pragma omp parallel for reduction(+ : bad, n) schedule(static)
         for (int64_t m = 0; m < (1 << 23); ++m) {
             for (int e = -4; e <= 3; ++e) {
                 const float v = ldexpf(u2f(0x3F800000u | (uint32_t)m), e);
-                const int a = e2m1_index((double)quot(v, hi, lo));
+                const int a = e2m1_index((double)mxq::quot(v, r));
                 const int b = e2m1_index_exact((double)v, (double)S);
                 ++n;
                 if (a != b) ++bad;
@@ -67,17 +57,11 @@ static long check_quot(long* cases)
     return bad;
 }
 
-/* the kernel's manual Round_SF (8-bit float, bias, clip) */
+/* the kernel's Round_SF on the bit pattern (clip, then mxq::sf_encode_bits) */
 static uint32_t sf_encode(float y, int bias, float maxv)
 {
     if (y > maxv) y = maxv;
-    const uint32_t b = f2u(y);
-    const uint32_t nrm = ((b + 0x7FFFFu + ((b >> 20) & 1u)) >> 20) - ((127u - bias) << 3);
-    const float magic = u2f((uint32_t)(127 + (1 - bias) + 20) << 23);
-    volatile float t = y + magic;
-    const uint32_t sub = f2u(t) - f2u(magic);
-    const float min_normal = u2f((uint32_t)(127 + 1 - bias) << 23);
-    return (y < min_normal) ? sub : nrm;
+    return bias == 7 ? mxq::sf_encode_bits<7>(y) : mxq::sf_encode_bits<15>(y);
 }
 static double sf_value(int bias, int c)
 {
@@ -102,7 +86,6 @@ static int sf_exact(double a, double M, int bias, int maxc)
 
 static long check_scale_encode(long* cases)
 {
-    const float sixth_hi = (float)(1.0 / 6.0), sixth_lo = (float)(1.0 / 6.0 - (double)(float)(1.0 / 6.0));
     long bad = 0, n = 0;
     for (int f = 0; f < 2; ++f) {
         const int bias = f ? 15 : 7, maxc = f ? 0xFE : 0x7E;
@@ -112,9 +95,8 @@ static long check_scale_encode(long* cases)
         for (int64_t m = 0; m < (1 << 23); m += 3) {
             for (int e = e_lo; e <= e_hi; ++e) {
                 const float a = ldexpf(u2f(0x3F800000u | (uint32_t)m), e);
-                volatile float p = a * sixth_lo;
-                const float y6 = fmaf(a, sixth_hi, p);
-                const float y4 = a * 0.25f;
+                const float y6 = mxq::sixth_of(a);
+                const float y4 = mxq::quarter_of(a);
                 n += 2;
                 if ((int)sf_encode(y6, bias, maxv) != sf_exact((double)a, 6.0, bias, maxc)) ++bad;
                 if ((int)sf_encode(y4, bias, maxv) != sf_exact((double)a, 4.0, bias, maxc)) ++bad;
@@ -132,8 +114,7 @@ static long check_pow2(long* cases)
 #pragma omp parallel for reduction(+ : bad, n) schedule(static)
     for (int64_t b = 0; b < 0x7F800000LL; b += 5) {
         const float a = u2f((uint32_t)b);
-        const int c = (int)(b >> 23) - 3 + (int)((b >> 22) & 1);
-        const int got = c < 0 ? 0 : c;
+        const int got = (int)mxq::pow2_code(a);
         int want = 0;
         if (a > 0.0f) {
             int ex;
@@ -155,12 +136,6 @@ static long check_pow2(long* cases)
 
 /* check 4: division by the per-tensor scale, reciprocal + one FMA refinement; the remainder is
  * taken with the opposite sign so that signed zeros survive (every bf16 value includes -0) */
-static float div_by_T(float v, float T, float rT)
-{
-    volatile float q0 = v * rT;
-    volatile float neg_rem = fmaf(q0, T, -v);
-    return fmaf(-neg_rem, rT, q0);
-}
 static long check_div(long* cases)
 {
     long bad = 0, n = 0;
@@ -172,8 +147,8 @@ static long check_div(long* cases)
         if (ti < 32) tm = 0x7FFFFEu - (uint32_t)ti;           /* near all-ones mantissas */
         const int te = (int)(NEXT() % 41) - 20;
         const float T = ldexpf(u2f(0x3F800000u | tm), te);
-        if (!(T >= 0x1p-20f && T <= 0x1p20f)) continue;
-        volatile float rT = 1.0f / T;
+        if (!mxq::fast_division_ok(T)) continue;
+        const float rT = 1.0f / T;
         for (uint32_t b = 0; b < 0x10000; ++b) {              /* every bf16 value */
             const float v = u2f(b << 16);
             if (isnan(v) || isinf(v)) continue;
@@ -181,7 +156,7 @@ static long check_div(long* cases)
             const float aq = fabsf(q);
             if (aq != 0.0f && (aq < 0x1p-78f || aq > 0x1p90f)) continue;   /* see below */
             ++n;
-            if (f2u(div_by_T(v, T, rT)) != f2u(q)) ++bad;
+            if (f2u(mxq::div_by_T(v, T, rT)) != f2u(q)) ++bad;
         }
         for (int k = 0; k < 30000; ++k) {                     /* random fp32 values */
             const uint32_t u = (uint32_t)NEXT();
@@ -195,7 +170,7 @@ static long check_div(long* cases)
              * or quantises to a signed zero with a squared residual that underflows to zero */
             if (aq < 0x1p-78f || aq > 0x1p90f) continue;
             ++n;
-            if (f2u(div_by_T(v, T, rT)) != f2u(q)) ++bad;
+            if (f2u(mxq::div_by_T(v, T, rT)) != f2u(q)) ++bad;
         }
     }
     *cases = n;
@@ -227,7 +202,7 @@ static long check_div_midpoints(long* cases)
 #pragma omp parallel for reduction(+ : bad, n) schedule(dynamic, 4096)
     for (int64_t Tp = (1 << 23); Tp < (1 << 24) - 1; ++Tp) {
         const float T = (float)Tp;
-        volatile float r = 1.0f / T;
+        const float r = 1.0f / T;
         for (int k = 24; k <= 25; ++k) {
             const int64_t lo = (k == 24) ? Tp : (1 << 23), hi = (k == 24) ? (1 << 24) : Tp;   /* V in [lo, hi) */
             int64_t x, y;
@@ -242,10 +217,52 @@ static long check_div_midpoints(long* cases)
                     if (!(M & 1)) continue;                     /* next to a float, not to a midpoint */
                     ++n;
                     const float v = (float)V;
-                    if (f2u(div_by_T(v, T, r)) != f2u(v / T)) ++bad;
+                    if (f2u(mxq::div_by_T(v, T, r)) != f2u(v / T)) ++bad;
                 }
             }
         }
+    }
+    *cases = n;
+    return bad;
+}
+
+/* check 6: the quotient for every finite bf16 value against every finite positive code of both
+ * scale formats (value and reciprocal exactly as the kernels' scale table holds them: many of
+ * these pairs are exact ties), incl. the sign of zero results */
+static long check_quot_bf16(long* cases)
+{
+    long bad = 0, n = 0;
+    for (int f = 0; f < 2; ++f) {
+        const int maxc = f ? 0xFE : 0x7E;
+#pragma omp parallel for reduction(+ : bad, n) schedule(static)
+        for (int c = 1; c <= maxc; ++c) {
+            const float S = f ? mxq::sf_decode_bias<15>((uint32_t)c) : mxq::sf_decode_bias<7>((uint32_t)c);
+            const mxq::Recip r = mxq::make_recip(S);
+            for (uint32_t b = 0; b < 0x10000u; ++b) {
+                const float v = u2f(b << 16);
+                if (isnan(v) || isinf(v)) continue;
+                const float y = mxq::quot(v, r);
+                ++n;
+                if (e2m1_index(fabs((double)y)) != e2m1_index_exact(fabs((double)v), (double)S)) ++bad;
+                if ((f2u(y) >> 31) != (b >> 15)) ++bad;
+            }
+        }
+    }
+    *cases = n;
+    return bad;
+}
+
+/* check 7: scale values built from bits against ldexp, every finite code of both formats; the
+ * range predicate of the fast division against its definition */
+static long check_decode(long* cases)
+{
+    long bad = 0, n = 0;
+    for (int c = 0; c <= 0x7E; ++c, ++n) bad += ((double)mxq::sf_decode_bias<7>((uint32_t)c) != sf_value(7, c));
+    for (int c = 0; c <= 0xFE; ++c, ++n) bad += ((double)mxq::sf_decode_bias<15>((uint32_t)c) != sf_value(15, c));
+    for (int64_t b = 0; b < 0x7F800000LL; b += 7, ++n) {
+        const float a = u2f((uint32_t)b);
+        const bool want = a != 0.0f && (a < 0x1p-40f || a > 0x1p90f);
+        bad += (mxq::fast_division_unsafe_amax(a) != want);
     }
     *cases = n;
     return bad;
@@ -259,5 +276,7 @@ int main(void)
     bad = check_pow2(&n);          printf("pow2_code cases=%ld bad=%ld\n", n, bad); total += bad;
     bad = check_div(&n);           printf("tensor_scale_division cases=%ld bad=%ld\n", n, bad); total += bad;
     bad = check_div_midpoints(&n); printf("tensor_scale_division_midpoints cases=%ld bad=%ld\n", n, bad); total += bad;
+    bad = check_quot_bf16(&n);     printf("bf16_quotient_decisions cases=%ld bad=%ld\n", n, bad); total += bad;
+    bad = check_decode(&n);        printf("scale_decode_and_range cases=%ld bad=%ld\n", n, bad); total += bad;
     return total == 0 ? 0 : 1;
 }
