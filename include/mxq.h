@@ -23,6 +23,7 @@
 #ifndef MXQ_H
 #define MXQ_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -158,6 +159,45 @@ MXQ_API int mxq_dequantize_hier(const uint8_t* codes, const uint8_t* scales,
  */
 MXQ_API int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
                       float* absmax_out, void* stream);
+
+/*
+ * mxq_tensor_absmax_acc -- the reduction as a running maximum, in ONE launch and with the
+ * shortest tail: *absmax_inout = max(*absmax_inout, max |x_i|).  For the dynamic-activation use of
+ * hierarchical scaling (Section 2), where the pre-pass is on the critical path, and for a tensor
+ * that arrives in several pieces (row shards: call once per piece on the same word).
+ *
+ *   absmax_inout  device, 1 float, 4-byte aligned.  Must hold +0 (or the non-negative maximum to
+ *                 be continued) when the kernel runs; nothing clears it here.
+ *   clear_word    device, 1 float, 4-byte aligned, or NULL.  Set to +0 by this call, to be the
+ *                 absmax_inout of a LATER call on the same stream: a caller that alternates
+ *                 between two words (this call's result in one, the next call's in the other)
+ *                 never needs a separate clear.  Must differ from absmax_inout.
+ * An empty tensor leaves absmax_inout untouched (and still clears clear_word).
+ * Errors as for mxq_tensor_absmax, plus INVALID_ARG when clear_word == absmax_inout.
+ */
+MXQ_API int mxq_tensor_absmax_acc(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                          float* absmax_inout, float* clear_word, void* stream);
+
+/*
+ * mxq_tensor_absmax_ws -- mxq_tensor_absmax in ONE launch (that one needs a second, tiny launch
+ * that clears the output word first) and without a precondition on the output word (unlike
+ * mxq_tensor_absmax_acc): the workgroups meet in a caller-owned workspace, and the one that
+ * arrives last writes the output.  One graph node instead of two; the tail of the kernel is
+ * longer than that of the other two forms (three dependent device-scope atomics), so on large
+ * tensors it is the slowest of the three (first stage of hierarchical scaling, Section 2).
+ *
+ *   workspace        device, at least mxq_tensor_absmax_workspace_size() bytes, 8-byte aligned.
+ *                    It must hold zeros before its first use (one hipMemset when it is allocated);
+ *                    every call leaves it zeroed again, so it can be reused from call to call.
+ *   workspace_bytes  size of the buffer behind `workspace`
+ * Calls that share one workspace must not overlap in time (give each concurrent stream its own).
+ * Errors as for mxq_tensor_absmax, plus INVALID_ARG for a NULL or too small workspace and
+ * ALIGNMENT for a misaligned one.
+ */
+#define MXQ_ABSMAX_WORKSPACE_BYTES 256
+MXQ_API size_t mxq_tensor_absmax_workspace_size(void);
+MXQ_API int mxq_tensor_absmax_ws(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                         float* absmax_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * mxq_clip_sse -- diagnostic of the paper's appendix ("Clipping only MSE"): for every block,

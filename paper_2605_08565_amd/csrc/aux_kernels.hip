@@ -164,23 +164,31 @@ hipError_t launch_dequant(const DequantArgs& a)
 }
 
 // Tensor abs-max.  |x| of finite fp32 values orders like the unsigned integer bits & 0x7fffffff,
-// so the reduction is an integer max; partial results meet in one 32-bit atomic max on the
-// output word, which a one-thread kernel clears first (no memset node, so the pair can be
-// captured in a graph).
+// so the reduction is an integer max; the workgroups' partial results meet in one 32-bit atomic
+// max on a device word.  Two closing schemes:
+//   * no workspace: the word is the caller's output, which a one-thread kernel clears first (a
+//     kernel, not a memset node, so the pair can be captured in a graph) -- two launches -- or
+//     which the caller guarantees to hold zero (or a maximum to be continued) -- one launch; that
+//     form can clear a second word on the way, the output of the caller's next call;
+//   * workspace (two words: accumulator, ticket; both zero between calls): every workgroup adds
+//     its maximum to the accumulator, then takes a ticket; the workgroup that draws the last
+//     ticket copies the accumulator to the output and returns both words to zero -- one launch.
 __global__ void absmax_clear_kernel(uint32_t* out) { *out = 0u; }
 
 // One workgroup of 1024 threads per compute unit walks tiles of 4 x 1024 vectors with four
 // independent 128-bit loads per lane in flight (16 MiB over the chip); the ragged last chunk (n
 // not a multiple of 8) is read element-wise by one lane.  Few, large workgroups because the
-// closing accesses to the one output word serialise at about 5 ns each, whatever their kind.
+// closing accesses to the one word serialise at about 5 ns each, whatever their kind.
 constexpr int kAbsItems = 4;
 constexpr int kAbsThreads = 1024;
 constexpr int kAbsMaxGrid = 256;
 
-template <int DT>
+template <int DT, bool TICKET>
 __global__ void __launch_bounds__(kAbsThreads)
-absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out)
+absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out, uint32_t* __restrict__ ws,
+              uint32_t* __restrict__ clear_word)
 {
+    if (clear_word && blockIdx.x == 0 && threadIdx.x == 0) *clear_word = 0u;      // for a LATER launch
     constexpr int64_t kVec = (DT == kBF16) ? 1 : 2;               // 128-bit vectors per chunk
     const int64_t n_vec = (n >> 3) * kVec;                         // complete vectors
     const int64_t tile = (int64_t)kAbsThreads * kAbsItems;
@@ -229,25 +237,55 @@ absmax_kernel(const void* __restrict__ x, int64_t n, uint32_t* __restrict__ out)
     if (threadIdx.x == 0) {
         uint32_t w = part[0];
         for (int i = 1; i < kAbsThreads / 64; ++i) w = max(w, part[i]);
-        // The word only grows, so a workgroup whose maximum does not exceed the value it reads
-        // (at device scope, past the per-CU cache) has nothing to add: after the first few
-        // workgroups almost none issues the atomic, which would otherwise serialise on one word.
-        if (w > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out, w);
+        if constexpr (!TICKET) {
+            // The word only grows during a call, so a workgroup whose maximum does not exceed the
+            // value it reads (at device scope, past the per-CU cache) has nothing to add: after
+            // the first few workgroups almost none issues the atomic max.
+            if (w > __hip_atomic_load(out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out, w);
+        } else {
+            // Read-modify-writes at device scope are performed at the one point all compute dies
+            // share.  The ticket is requested only after the value returned by the max has arrived
+            // (its increment depends on it), i.e. after the max was performed there; the workgroup
+            // that draws the last ticket therefore exchanges out a word that already holds every
+            // other workgroup's contribution.  No cache-wide fence is needed (one costs several
+            // microseconds here, more than the second launch it would save).
+            const uint32_t before = atomicMax(ws, w);
+            const uint32_t ticket = atomicAdd(ws + 1, 1u + (before >> 31));      // bit 31 is never set
+            if (ticket == gridDim.x - 1u) {
+                *out = atomicExch(ws, 0u);
+                atomicExch(ws + 1, 0u);
+            }
+        }
     }
 }
 
-hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, hipStream_t stream)
+// `ws`: the two-word workspace of the ticket scheme, or NULL.  `accumulate` (without ws): the output
+// word is not cleared first; `clear_word` (accumulate only, may be NULL) is set to zero instead.
+hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, uint32_t* ws, bool accumulate,
+                         float* clear_word, hipStream_t stream)
 {
-    hipLaunchKernelGGL(absmax_clear_kernel, dim3(1), dim3(1), 0, stream, (uint32_t*)out);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || n == 0) return e;
+    if (accumulate && n == 0) {
+        if (!clear_word) return hipSuccess;
+        hipLaunchKernelGGL(absmax_clear_kernel, dim3(1), dim3(1), 0, stream, (uint32_t*)clear_word);
+        return hipGetLastError();
+    }
+    if ((!ws && !accumulate) || n == 0) {
+        hipLaunchKernelGGL(absmax_clear_kernel, dim3(1), dim3(1), 0, stream, (uint32_t*)out);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess || n == 0) return e;
+    }
     const int64_t n_tiles = ((n + 7) / 8 + kAbsThreads * kAbsItems - 1) / (kAbsThreads * kAbsItems);
     const int64_t capw = kAbsMaxGrid;
-    const int grid = (int)(n_tiles < 1 ? 1 : (n_tiles < capw ? n_tiles : capw));
-    if (dtype == kBF16)
-        hipLaunchKernelGGL((absmax_kernel<kBF16>), dim3(grid), dim3(kAbsThreads), 0, stream, x, n, (uint32_t*)out);
-    else
-        hipLaunchKernelGGL((absmax_kernel<kF32>), dim3(grid), dim3(kAbsThreads), 0, stream, x, n, (uint32_t*)out);
+    const dim3 grid((unsigned)(n_tiles < 1 ? 1 : (n_tiles < capw ? n_tiles : capw))), block(kAbsThreads);
+    uint32_t* o = (uint32_t*)out;
+    uint32_t* cw = (uint32_t*)clear_word;
+    if (dtype == kBF16) {
+        if (ws) hipLaunchKernelGGL((absmax_kernel<kBF16, true>), grid, block, 0, stream, x, n, o, ws, cw);
+        else hipLaunchKernelGGL((absmax_kernel<kBF16, false>), grid, block, 0, stream, x, n, o, ws, cw);
+    } else {
+        if (ws) hipLaunchKernelGGL((absmax_kernel<kF32, true>), grid, block, 0, stream, x, n, o, ws, cw);
+        else hipLaunchKernelGGL((absmax_kernel<kF32, false>), grid, block, 0, stream, x, n, o, ws, cw);
+    }
     return hipGetLastError();
 }
 

@@ -5,6 +5,7 @@
 #include "mxq_launch.hpp"
 
 #include <cmath>
+#include <cstddef>
 #include <cstdint>
 
 namespace {
@@ -132,8 +133,8 @@ int mxq_dequantize_hier(const uint8_t* codes, const uint8_t* scales,
                              x_out, out_dtype, stream);
 }
 
-int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
-                      float* absmax_out, void* stream)
+static int absmax_common(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                         float* absmax_out, uint32_t* ws, bool accumulate, float* clear_word, void* stream)
 {
     if (rows < 0 || cols < 0 || !absmax_out) return MXQ_ERR_INVALID_ARG;
     if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
@@ -141,8 +142,32 @@ int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
     const int64_t n = rows * cols;
     if (n > 0 && !x) return MXQ_ERR_INVALID_ARG;
     if ((n > 0 && !aligned(x, 16)) || !aligned(absmax_out, 4)) return MXQ_ERR_ALIGNMENT;
-    return mxq::launch_absmax(x, n, x_dtype, absmax_out, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? MXQ_OK : MXQ_ERR_HIP;
+    if (!aligned(clear_word, 4)) return MXQ_ERR_ALIGNMENT;
+    if (clear_word == absmax_out) return MXQ_ERR_INVALID_ARG;
+    return mxq::launch_absmax(x, n, x_dtype, absmax_out, ws, accumulate, clear_word,
+                              static_cast<hipStream_t>(stream)) == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
+}
+
+int mxq_tensor_absmax(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                      float* absmax_out, void* stream)
+{
+    return absmax_common(x, rows, cols, x_dtype, absmax_out, nullptr, false, nullptr, stream);
+}
+
+int mxq_tensor_absmax_acc(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                          float* absmax_inout, float* clear_word, void* stream)
+{
+    return absmax_common(x, rows, cols, x_dtype, absmax_inout, nullptr, true, clear_word, stream);
+}
+
+size_t mxq_tensor_absmax_workspace_size(void) { return MXQ_ABSMAX_WORKSPACE_BYTES; }
+
+int mxq_tensor_absmax_ws(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                         float* absmax_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!workspace || workspace_bytes < MXQ_ABSMAX_WORKSPACE_BYTES) return MXQ_ERR_INVALID_ARG;
+    if (!aligned(workspace, 8)) return MXQ_ERR_ALIGNMENT;
+    return absmax_common(x, rows, cols, x_dtype, absmax_out, static_cast<uint32_t*>(workspace), false, nullptr, stream);
 }
 
 int mxq_clip_sse(const void* x, const uint8_t* scales, int64_t rows, int64_t cols, int block,

@@ -51,6 +51,7 @@ hipError_t launch_clip_sse(const void* x, const uint8_t* scales, int64_t n, int 
 hipError_t launch_histogram(const uint8_t* codes, const uint8_t* scales, int64_t n, int block,
                             unsigned long long* elem_hist, unsigned long long* scale_hist,
                             hipStream_t stream);
-hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, hipStream_t stream);
+hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, uint32_t* ws, bool accumulate,
+                         float* clear_word, hipStream_t stream);
 
 }  // namespace mxq

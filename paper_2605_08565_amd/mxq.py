@@ -49,6 +49,12 @@ def lib() -> ctypes.CDLL:
     L.mxq_dequantize_hier.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, i32, vp]
     L.mxq_tensor_absmax.restype = i32
     L.mxq_tensor_absmax.argtypes = [vp, i64, i64, i32, vp, vp]
+    L.mxq_tensor_absmax_acc.restype = i32
+    L.mxq_tensor_absmax_acc.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+    L.mxq_tensor_absmax_workspace_size.restype = ctypes.c_size_t
+    L.mxq_tensor_absmax_workspace_size.argtypes = []
+    L.mxq_tensor_absmax_ws.restype = i32
+    L.mxq_tensor_absmax_ws.argtypes = [vp, i64, i64, i32, vp, vp, ctypes.c_size_t, vp]
     L.mxq_clip_sse.restype = i32
     L.mxq_clip_sse.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
     L.mxq_histogram.restype = i32
@@ -184,8 +190,32 @@ def dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt:
     return out
 
 
-def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
-    """mxq_tensor_absmax: one-element fp32 device tensor holding max |x|."""
+def absmax_workspace(device="cuda") -> torch.Tensor:
+    """A zeroed workspace for tensor_absmax(..., workspace=...); reusable from call to call."""
+    return torch.zeros(int(lib().mxq_tensor_absmax_workspace_size()), dtype=torch.uint8, device=device)
+
+
+def tensor_absmax_acc(x: torch.Tensor, inout: torch.Tensor, clear_word: torch.Tensor | None = None,
+                      stream=None) -> torch.Tensor:
+    """mxq_tensor_absmax_acc: inout = max(inout, max |x|) in one launch; `clear_word` (optional
+    one-element fp32 tensor) is zeroed for a later call."""
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor on the GPU")
+    _need(inout, 4, "inout", torch.float32)
+    if clear_word is not None:
+        _need(clear_word, 4, "clear_word", torch.float32)
+    rows = x.shape[0] if x.dim() == 2 else 1
+    cols = x.shape[1] if x.dim() == 2 else x.numel()
+    _check(lib().mxq_tensor_absmax_acc(x.data_ptr(), rows, cols, _dtype_code(x), inout.data_ptr(),
+                                       clear_word.data_ptr() if clear_word is not None else None,
+                                       _stream_ptr(stream)))
+    return inout
+
+
+def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None,
+                  workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """mxq_tensor_absmax: one-element fp32 device tensor holding max |x|.  With a `workspace`
+    (from absmax_workspace) mxq_tensor_absmax_ws, the one-launch form."""
     if not x.is_cuda or not x.is_contiguous():
         raise ValueError("x must be a contiguous tensor on the GPU")
     if out is None:
@@ -193,6 +223,11 @@ def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None)
     _need(out, 4, "out", torch.float32)
     rows = x.shape[0] if x.dim() == 2 else 1
     cols = x.shape[1] if x.dim() == 2 else x.numel()
+    if workspace is not None:
+        _need(workspace, 0, "workspace", torch.uint8)
+        _check(lib().mxq_tensor_absmax_ws(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
+                                          workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+        return out
     _check(lib().mxq_tensor_absmax(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
                                    _stream_ptr(stream)))
     return out

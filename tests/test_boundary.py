@@ -28,7 +28,8 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_clip_sse",
+    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc",
+                            "mxq_tensor_absmax_workspace_size", "mxq_clip_sse",
                             "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
                             "mxq_num_candidates", "mxq_status_string"])
@@ -134,6 +135,22 @@ def test_argument_validation_without_a_launch(mxq):
     assert L.mxq_tensor_absmax(None, 4, 4, 0, P, None) == mxq.ERR_INVALID_ARG
     assert L.mxq_tensor_absmax(P, 4, 4, 5, P, None) == mxq.ERR_INVALID_ARG
     assert L.mxq_tensor_absmax(P + 4, 4, 4, 0, P, None) == mxq.ERR_ALIGNMENT
+
+    assert L.mxq_tensor_absmax_acc(P, 4, 4, 0, None, None, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_acc(P, 4, 4, 0, P, P, None) == mxq.ERR_INVALID_ARG       # same word
+    assert L.mxq_tensor_absmax_acc(P, 4, 4, 0, P, P + 6, None) == mxq.ERR_ALIGNMENT
+    assert L.mxq_tensor_absmax_acc(None, 4, 4, 0, P, P + 4, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_acc(None, 0, 4, 0, P, None, None) == mxq.OK                # nothing to do
+
+    wsz = L.mxq_tensor_absmax_workspace_size()
+    assert wsz == 256
+    assert L.mxq_tensor_absmax_ws(P, 4, 4, 0, P, None, wsz, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_ws(P, 4, 4, 0, P, P, wsz - 1, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_ws(P, 4, 4, 0, P, P + 4, wsz, None) == mxq.ERR_ALIGNMENT
+    assert L.mxq_tensor_absmax_ws(P, 4, 4, 0, None, P, wsz, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_ws(None, 4, 4, 0, P, P, wsz, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_ws(P, 4, 4, 7, P, P, wsz, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_ws(P + 8, 4, 4, 1, P, P, wsz, None) == mxq.ERR_ALIGNMENT
 
 
 def test_binding_fails_loudly_without_the_library(mxq, monkeypatch):

@@ -360,6 +360,60 @@ def test_tensor_absmax(oracle, mxq):
         assert got == oracle.tensor_absmax(x)
 
 
+def test_tensor_absmax_running_maximum(oracle, mxq):
+    """mxq_tensor_absmax_acc: two words used alternately, each call clearing the other one's word
+    (no clear launch anywhere); a tensor fed in row shards accumulates to the whole tensor's
+    maximum; an empty tensor leaves the word alone."""
+    words = torch.zeros(2, dtype=torch.float32, device="cuda")
+    big = W.config3()
+    cases = [big, W.bf16_bits_to_f32(big[:2048]), W.config1()[:37] * np.float32(0.01), W.student_t_weights(33, 1000, seed=9),
+             W.normal_f32(1, 6, 3) * np.float32(1e-3), np.zeros((3, 40), np.float32), big[:7]]
+    got = []
+    for k, x_np in enumerate(cases):            # no host synchronisation between the calls
+        mxq.tensor_absmax_acc(mxq.from_bits(x_np), words[k % 2:k % 2 + 1], clear_word=words[(k + 1) % 2:(k + 1) % 2 + 1])
+        got.append(words[k % 2:k % 2 + 1].clone())
+    for k, x_np in enumerate(cases):
+        assert float(got[k].cpu()[0]) == oracle.tensor_absmax(x_np), k
+    acc = torch.zeros(1, dtype=torch.float32, device="cuda")
+    xb = mxq.from_bits(big)
+    for r0 in range(0, big.shape[0], 1000):
+        mxq.tensor_absmax_acc(xb[r0:r0 + 1000], acc)
+    assert float(acc.cpu()[0]) == oracle.tensor_absmax(big)
+    mxq.tensor_absmax_acc(torch.empty((0, 8), dtype=torch.float32, device="cuda"), acc, clear_word=words[0:1])
+    assert float(acc.cpu()[0]) == oracle.tensor_absmax(big) and float(words.cpu()[0]) == 0.0
+
+
+def test_tensor_absmax_one_launch(oracle, mxq):
+    """mxq_tensor_absmax_ws: one workspace reused over tensors of very different sizes (1 to 256
+    workgroups, ragged tails, both dtypes, an empty tensor, decreasing maxima so that a value
+    left behind by an earlier call would show), stale output words, and the workspace back at
+    zero after every call."""
+    ws = mxq.absmax_workspace()
+    out = torch.full((1,), 123.0, dtype=torch.float32, device="cuda")
+    big = W.config3()
+    cases = [big, W.bf16_bits_to_f32(big[:2048]), W.config1()[:37] * np.float32(0.01), W.student_t_weights(33, 1000, seed=9),
+             W.normal_f32(1, 6, 3) * np.float32(1e-3), np.zeros((3, 40), np.float32), big[:7],
+             W.normal_f32(2049, 4099, 5) * np.float32(1e-5)]
+    for x_np in cases:
+        print(f"[absmax-ws] shape={x_np.shape} dtype={x_np.dtype}", flush=True)
+        mxq.tensor_absmax(mxq.from_bits(x_np), out=out, workspace=ws)
+        assert float(out.cpu()[0]) == oracle.tensor_absmax(x_np)
+        assert int(ws.cpu().to(torch.int64).sum()) == 0
+    empty = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    mxq.tensor_absmax(empty, out=out, workspace=ws)
+    assert float(out.cpu()[0]) == 0.0
+    # back-to-back calls on one stream without a host synchronisation in between
+    xs = [mxq.from_bits(c) for c in cases[:4]]
+    outs = torch.zeros(16, dtype=torch.float32, device="cuda")
+    for rep in range(4):
+        for i, x in enumerate(xs):
+            mxq.tensor_absmax(x, out=outs[4 * rep + i:4 * rep + i + 1], workspace=ws)
+    got = outs.cpu().numpy()
+    for rep in range(4):
+        for i in range(4):
+            assert got[4 * rep + i] == oracle.tensor_absmax(cases[i])
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 
 def sample_rows(n_rows, k, seed):
@@ -641,9 +695,12 @@ def test_graph_capture_and_replay(oracle, mxq):
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
+    ws = mxq.absmax_workspace()
+    amax2 = torch.zeros(1, dtype=torch.float32, device="cuda")
     with torch.cuda.graph(g):
         mxq.tensor_absmax(x, out=amax)
-        mxq.quantize_hier(x, block, 1, 2, amax, tensor_scale_out=t_dev, codes_out=codes_h, scales_out=scales_h,
+        mxq.tensor_absmax(x, out=amax2, workspace=ws)                 # the one-launch form
+        mxq.quantize_hier(x, block, 1, 2, amax2, tensor_scale_out=t_dev, codes_out=codes_h, scales_out=scales_h,
                           sse_out=sse_h)
         mxq.quantize(x, block, 1, 2, codes_out=codes, scales_out=scales, sse_out=sse)
         mxq.dequantize(codes, scales, block, 1, 1.0, out=deq)
@@ -655,7 +712,7 @@ def test_graph_capture_and_replay(oracle, mxq):
         g.replay()
         torch.cuda.synchronize()
         oc, os_, oe = oracle.quantize(x_np, block, 1, 2)
-        assert float(amax.cpu()[0]) == oracle.tensor_absmax(x_np)
+        assert float(amax.cpu()[0]) == oracle.tensor_absmax(x_np) == float(amax2.cpu()[0])
         assert (codes.cpu().numpy() == oc).all() and (scales.cpu().numpy() == os_).all()
         assert (sse.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
         want = oracle.dequantize(oc, os_, block, 1, 1.0, oracle.DT_BF16)
