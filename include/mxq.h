@@ -18,7 +18,8 @@
  *     or prints.  Inputs are assumed finite: NaN/Inf elements give unspecified codes, never
  *     a fault.
  *   - Outputs are overwritten in full; they must not alias the input.
- *   - Calls are re-entrant; there is no global mutable state.
+ *   - Calls are re-entrant; there is no global mutable state (one documented exception:
+ *     mxq_tensor_absmax_static).
  */
 #ifndef MXQ_H
 #define MXQ_H
@@ -198,6 +199,27 @@ MXQ_API int mxq_tensor_absmax_acc(const void* x, int64_t rows, int64_t cols, int
 MXQ_API size_t mxq_tensor_absmax_workspace_size(void);
 MXQ_API int mxq_tensor_absmax_ws(const void* x, int64_t rows, int64_t cols, int x_dtype,
                          float* absmax_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * mxq_tensor_absmax_static -- mxq_tensor_absmax_ws for callers that can neither allocate device
+ * memory nor carry a workspace around: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels, same result; the two-word workspace is a
+ * 256-byte array inside the library's own device image (one copy per GPU, held until the process
+ * ends).  The call allocates and frees nothing.
+ *
+ *   - rows*cols may not exceed MXQ_ABSMAX_STATIC_MAX_ELEMENTS (2^40): MXQ_ERR_UNSUPPORTED beyond.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race and may both return wrong maxima; calls on one stream, or
+ *     otherwise ordered, are safe.  Each call returns the array to zero, which is the state the
+ *     next call needs.  This is the library's only global state.
+ *   - The device must be current.  The first call on each device looks the array's address up
+ *     (hipGetSymbolAddress); make that call outside graph capture.
+ * Other arguments and errors as for mxq_tensor_absmax; MXQ_ERR_HIP also when the address
+ * look-up fails.
+ */
+#define MXQ_ABSMAX_STATIC_MAX_ELEMENTS ((int64_t)1 << 40)
+MXQ_API int mxq_tensor_absmax_static(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                             float* absmax_out, void* stream);
 
 /*
  * mxq_clip_sse -- diagnostic of the paper's appendix ("Clipping only MSE"): for every block,

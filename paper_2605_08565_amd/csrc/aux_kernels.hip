@@ -3,6 +3,8 @@
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"
 
+#include <mutex>
+
 namespace mxq {
 
 using bf16x2 = __bf16 __attribute__((ext_vector_type(2)));
@@ -287,6 +289,46 @@ hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, uint32
         else hipLaunchKernelGGL((absmax_kernel<kF32, false>), grid, block, 0, stream, x, n, o, ws, cw);
     }
     return hipGetLastError();
+}
+
+// Workspace of the entry point that may not allocate and takes no workspace argument: the two
+// words of the ticket scheme (the rest is padding to the alignment) live in the library's own
+// device image, one copy per GPU, zero when the image is loaded and returned to zero by every call.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the address it yields for
+// the current device is what kernels and launches are given.
+constexpr int kStaticScratchWords = 64;
+static __device__ __align__(256) uint32_t scratch[kStaticScratchWords];
+
+constexpr int kMaxDevices = 64;
+static uint32_t* g_scratch_ptr[kMaxDevices];      // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch`, resolved once per device.
+static hipError_t static_scratch(uint32_t** ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<uint32_t*>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+// The ticket scheme on the library's own workspace: no allocation, no workspace argument.
+hipError_t launch_absmax_static(const void* x, int64_t n, int dtype, float* out, hipStream_t stream)
+{
+    uint32_t* ws = nullptr;
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return e;
+    return launch_absmax(x, n, dtype, out, ws, false, nullptr, stream);
 }
 
 }  // namespace mxq

@@ -170,6 +170,20 @@ int mxq_tensor_absmax_ws(const void* x, int64_t rows, int64_t cols, int x_dtype,
     return absmax_common(x, rows, cols, x_dtype, absmax_out, static_cast<uint32_t*>(workspace), false, nullptr, stream);
 }
 
+int mxq_tensor_absmax_static(const void* x, int64_t rows, int64_t cols, int x_dtype,
+                             float* absmax_out, void* stream)
+{
+    if (rows < 0 || cols < 0 || !absmax_out) return MXQ_ERR_INVALID_ARG;
+    if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
+    if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
+    const int64_t n = rows * cols;
+    if (n > MXQ_ABSMAX_STATIC_MAX_ELEMENTS) return MXQ_ERR_UNSUPPORTED;
+    if (n > 0 && !x) return MXQ_ERR_INVALID_ARG;
+    if ((n > 0 && !aligned(x, 16)) || !aligned(absmax_out, 4)) return MXQ_ERR_ALIGNMENT;
+    return mxq::launch_absmax_static(x, n, x_dtype, absmax_out, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MXQ_OK : MXQ_ERR_HIP;
+}
+
 int mxq_clip_sse(const void* x, const uint8_t* scales, int64_t rows, int64_t cols, int block,
                  int elem_fmt, int scale_fmt, float tensor_scale, float* clip_sse_out,
                  int x_dtype, void* stream)

@@ -53,5 +53,6 @@ hipError_t launch_histogram(const uint8_t* codes, const uint8_t* scales, int64_t
                             hipStream_t stream);
 hipError_t launch_absmax(const void* x, int64_t n, int dtype, float* out, uint32_t* ws, bool accumulate,
                          float* clear_word, hipStream_t stream);
+hipError_t launch_absmax_static(const void* x, int64_t n, int dtype, float* out, hipStream_t stream);
 
 }  // namespace mxq

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
     L.mxq_tensor_absmax_workspace_size.argtypes = []
     L.mxq_tensor_absmax_ws.restype = i32
     L.mxq_tensor_absmax_ws.argtypes = [vp, i64, i64, i32, vp, vp, ctypes.c_size_t, vp]
+    L.mxq_tensor_absmax_static.restype = i32
+    L.mxq_tensor_absmax_static.argtypes = [vp, i64, i64, i32, vp, vp]
     L.mxq_clip_sse.restype = i32
     L.mxq_clip_sse.argtypes = [vp, vp, i64, i64, i32, i32, i32, f32, vp, i32, vp]
     L.mxq_histogram.restype = i32
@@ -230,6 +232,19 @@ def tensor_absmax(x: torch.Tensor, out: torch.Tensor | None = None, stream=None,
         return out
     _check(lib().mxq_tensor_absmax(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
                                    _stream_ptr(stream)))
+    return out
+
+
+def tensor_absmax_static(x: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """mxq_tensor_absmax_static: one launch on the library's own workspace; allocates nothing
+    (the output tensor is the caller's).  Calls that overlap on one GPU race."""
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous tensor on the GPU")
+    _need(out, 4, "out", torch.float32)
+    rows = x.shape[0] if x.dim() == 2 else 1
+    cols = x.shape[1] if x.dim() == 2 else x.numel()
+    _check(lib().mxq_tensor_absmax_static(x.data_ptr(), rows, cols, _dtype_code(x), out.data_ptr(),
+                                          _stream_ptr(stream)))
     return out
 
 

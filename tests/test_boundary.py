@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc",
+    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc", "mxq_tensor_absmax_static",
                             "mxq_tensor_absmax_workspace_size", "mxq_clip_sse",
                             "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
@@ -136,6 +136,12 @@ def test_argument_validation_without_a_launch(mxq):
     assert L.mxq_tensor_absmax(P, 4, 4, 5, P, None) == mxq.ERR_INVALID_ARG
     assert L.mxq_tensor_absmax(P + 4, 4, 4, 0, P, None) == mxq.ERR_ALIGNMENT
 
+    # the allocation-free form: argument errors and the size limit come before any HIP call
+    assert L.mxq_tensor_absmax_static(P, 4, 4, 0, None, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_static(None, 4, 4, 0, P, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_static(P, 4, 4, 3, P, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_tensor_absmax_static(P + 4, 4, 4, 0, P, None) == mxq.ERR_ALIGNMENT
+    assert L.mxq_tensor_absmax_static(P, 1 << 21, (1 << 19) + 8, 0, P, None) == mxq.ERR_UNSUPPORTED
     assert L.mxq_tensor_absmax_acc(P, 4, 4, 0, None, None, None) == mxq.ERR_INVALID_ARG
     assert L.mxq_tensor_absmax_acc(P, 4, 4, 0, P, P, None) == mxq.ERR_INVALID_ARG       # same word
     assert L.mxq_tensor_absmax_acc(P, 4, 4, 0, P, P + 6, None) == mxq.ERR_ALIGNMENT
