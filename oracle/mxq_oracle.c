@@ -331,7 +331,10 @@ int orc_quantize(const void* x, int x_dtype, int64_t rows, int64_t cols, int blo
     if (rows < 0 || cols < 0 || !valid_block(block) || cols % block != 0) return -1;
     if (x_dtype != ORC_DT_BF16 && x_dtype != ORC_DT_F32) return -1;
     if (scale_fmt < 0 || scale_fmt > 2 || recipe < 0 || recipe > 4) return -1;
-    if (scale_fmt == ORC_SCALE_E8M0 && recipe >= ORC_4OVER6) return -1;
+    /* Eq. 4 chooses between two roundings of amax / M, which the floor rule of Eq. 1 does not
+     * define; the brute-force search "over possible scaling factors" applies to the power-of-two
+     * format as it stands: all 255 bytes 0x00 .. 0xFE are finite positive values. */
+    if (scale_fmt == ORC_SCALE_E8M0 && (recipe == ORC_4OVER6 || recipe == ORC_4OVER6_PZ)) return -1;
     if (!(tensor_scale > 0.0f) || isinf(tensor_scale)) return -1;
 
     int64_t nb = rows * cols / block;

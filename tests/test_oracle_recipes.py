@@ -119,6 +119,38 @@ def test_brute_force_exhaustive_pairs_ue5m3(oracle):
         assert exE[i, 0] == pytest.approx(sse_int * 2.0 ** (2 * unit), rel=1e-15)
 
 
+def test_brute_force_exhaustive_pairs_e8m0(oracle):
+    """The same against the 255 power-of-two scales.  The independent search walks the bytes whose
+    value lies in [2^-30, 2^20] (the others either clip every non-zero lattice value or send all of
+    them to zero, so they can only tie with or lose to a byte inside the range)."""
+    lo, hi = 127 - 30, 127 + 20
+    svals = [0.0] * lo + [2.0 ** (c - 127) for c in range(lo, hi + 1)]
+    lat = [v for v in LATTICE[::2] if v != 0.0] + [300.0]
+    signed = sorted(set(lat + [-v for v in lat]))
+    pairs = np.array([[a, b] for a in signed for b in signed], np.float32)
+    cE, sE, _, exE = oracle.quantize(pairs, 2, oracle.SCALE_E8M0, oracle.BRUTE,
+                                     sel_mode=oracle.SEL_EXACT, want_exact=True)
+    cP, sP, sseP, exP = oracle.quantize(pairs, 2, oracle.SCALE_E8M0, oracle.BRUTE, want_exact=True)
+    unit = -60
+    for i, (a, b) in enumerate(pairs):
+        code, sse_int, mags = exact_block_search([float(a), float(b)], svals, unit)
+        assert sE[i, 0] == code, (a, b)
+        assert [cE[i, 0] & 7, (cE[i, 0] >> 4) & 7] == mags
+        assert exE[i, 0] == pytest.approx(sse_int * 2.0 ** (2 * unit), rel=1e-15)
+        assert exP[i, 0] <= exE[i, 0] * (1 + 1e-6) + 1e-300
+    # the floor rule of Eq. 1 is one of the candidates, so the search can only improve on it
+    x = W.student_t_weights(64, 512, seed=31)
+    for b in (2, 8, 32):
+        e_abs = oracle.quantize(x, b, oracle.SCALE_E8M0, oracle.ABSMAX)[2]
+        e_bf = oracle.quantize(x, b, oracle.SCALE_E8M0, oracle.BRUTE)[2]
+        assert (e_bf <= e_abs).all() and (e_bf < e_abs).any()
+    # an all-zero block: every scale gives SSE 0, the lowest byte wins
+    z = oracle.quantize(np.zeros((1, 4), np.float32), 4, oracle.SCALE_E8M0, oracle.BRUTE)
+    assert z[1][0, 0] == 0 and z[2][0, 0] == 0.0
+    with pytest.raises(ValueError):
+        oracle.quantize(x, 8, oracle.SCALE_E8M0, oracle.FOUR_OVER_SIX)
+
+
 def test_streaming_recipes_against_exact_integers(oracle):
     """abs-max / prevent-zero / 4-over-6 on blocks of 4 from the lattice: the scale is the
     E4M3 value nearest to amax/M (ties to even, exact rationals), the codes are the nearest
