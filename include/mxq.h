@@ -63,12 +63,14 @@ typedef enum { MXQ_SCALE_E8M0 = 0, MXQ_SCALE_E4M3 = 1, MXQ_SCALE_UE5M3 = 2 } mxq
  *              tie (Eq. 4).
  *   4OVER6_PZ  both candidates clamped by Eq. 3 first (Fig. 1(d) of the paper).
  *   BRUTE      every finite, strictly positive scale code is tried; the lowest code of
- *              minimal SSE is kept (brute-force paragraph, Section 2).
+ *              minimal SSE is kept (brute-force paragraph, Section 2).  126 candidates for
+ *              E4M3, 254 for UE5M3, the 255 powers of two 2^(byte-127), byte 0 .. 254, for E8M0.
  *   BRUTE_PRUNED  the same result as BRUTE, bit for bit, but candidates that provably cannot
  *              win are skipped (scales so large that the block quantises to zero, scales so
  *              small that the clipping error of the abs-max element alone exceeds the SSE of
  *              the abs-max scale).  A step toward cheaper near-optimal selection (Conclusion).
- * 4OVER6*, BRUTE* with E8M0 return MXQ_ERR_UNSUPPORTED. */
+ * 4OVER6* and BRUTE_PRUNED with E8M0 return MXQ_ERR_UNSUPPORTED (Eq. 4 rounds amax / M to the
+ * scale format, which the floor rule of Eq. 1 does not define). */
 typedef enum {
     MXQ_RECIPE_ABSMAX = 0,
     MXQ_RECIPE_ABSMAX_PZ = 1,
@@ -107,6 +109,23 @@ MXQ_API int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
                  int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
                  uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
                  int x_dtype, void* stream);
+
+/*
+ * mxq_quantize_clip -- mxq_quantize with one more per-block output, the clipping-only part of
+ * the block SSE (appendix figure "Clipping only MSE"): the sum, over the elements that saturate
+ * at the largest E2M1 magnitude (|v_i / S| > 6) under the SELECTED scale, of their squared
+ * residuals; elements that do not clip contribute +0; same fp32 tree as the block SSE.  Equal,
+ * bit for bit, to mxq_clip_sse run afterwards on the scales this call writes, without the second
+ * read of x (4 / block extra bytes per element instead of sizeof(x) + 5 / block).
+ *
+ *   clip_sse_out  device, rows*cols/block floats, 16-byte aligned, row-major; NULL to skip (then
+ *                 the call is mxq_quantize)
+ * Everything else, and all errors, as for mxq_quantize.
+ */
+MXQ_API int mxq_quantize_clip(const void* x, int64_t rows, int64_t cols, int block,
+                      int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
+                      uint8_t* codes_out, uint8_t* scales_out, float* sse_out, float* clip_sse_out,
+                      int x_dtype, void* stream);
 
 /*
  * mxq_quantize_hier -- hierarchical scaling without a round trip to the host (the two-stage
@@ -257,7 +276,7 @@ MXQ_API float mxq_tensor_scale_from_absmax(float absmax, int elem_fmt, int scale
 MXQ_API float mxq_scale_decode(int scale_fmt, uint8_t code);
 
 /* Host helper: number of candidates BRUTE tries (finite positive codes): 126 for E4M3,
- * 254 for UE5M3, 255 for E8M0 (not searched); -1 on a bad enum. */
+ * 254 for UE5M3, 255 for E8M0; -1 on a bad enum. */
 MXQ_API int mxq_num_candidates(int scale_fmt);
 
 /* Host helper: static, human-readable name of a status code. */

@@ -11,6 +11,9 @@
 // FMA because the product is exact.  Candidates are visited in ascending code order, one
 // binade (8 codes) at a time, so a strict "less than" between binades and the first position
 // inside one keep the lowest code on ties.
+//
+// Power-of-two scales (E8M0, every byte 0x00 .. 0xFE is a finite positive value, 255 candidates)
+// need no quotient at all: the conversion instruction divides by 2^k itself.
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"
 
@@ -207,68 +210,123 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t& lo_w
     hi_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_all);
 }
 
-// Search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE.
+// Value of a power-of-two scale byte (0 .. 254); 2^-127 is a sub-normal float.
+__device__ __forceinline__ float pow2_scale(uint32_t code)
+{
+    return (code == 0u) ? u2f(0x00400000u) : u2f(code << 23);
+}
+
+// The 8 codes code0 .. code0 + 7 of the power-of-two format; code 255 is not a number.
+template <int B, int POS, class G>
+__device__ __forceinline__ void try_pow2_from(const float (&v)[8], uint32_t code0, G& g)
+{
+    if constexpr (POS < 8) {
+        if (POS < 7 || code0 + 7u <= 254u) try_candidate<B, 0, POS>(v, v, pow2_scale(code0 + POS), g);
+        try_pow2_from<B, POS + 1>(v, code0, g);
+    }
+}
+
+// Search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE, and
+// the scale value of every winner.
 template <int B, int FMT, bool PRUNE>
-__device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
+__device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& packed, BruteState<B>& st,
+                                             float (&S_best)[BruteState<B>::NBLK])
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int EPB = (B < 8) ? B : 8;
-    constexpr int bias = ScaleFmt<FMT>::kBias;
-    constexpr int emin = 1 - bias;                                      // exponent of the first binade
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = (FMT == kE8M0) ? 0u : 1u; }
 
-    uint32_t lo_w = 1u, hi_w = (uint32_t)ScaleFmt<FMT>::kMaxCode;
-    if constexpr (PRUNE) prune_window<B, FMT>(v, lo_w, hi_w);
+    if constexpr (FMT == kE8M0) {
+        static_assert(!PRUNE, "the pruned search covers the 8-bit floating-point scale formats only");
+        for (uint32_t code0 = 0u; code0 < 256u; code0 += 8u) {
+            GroupArgMin<B> g;
+            g.begin();
+            try_pow2_from<B, 0>(v, code0, g);
+            g.end(st, code0);
+        }
+        // codes of the winners: the conversion applies each block's own power of two
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) S_best[k] = pow2_scale(st.best_code[k]);
+        packed = e2m1_pack8_scales<EPB>(v, S_best);
+    } else {
+        constexpr int bias = ScaleFmt<FMT>::kBias;
+        constexpr int emin = 1 - bias;                                  // exponent of the first binade
 
-    float w[8][8];
+        uint32_t lo_w = 1u, hi_w = (uint32_t)ScaleFmt<FMT>::kMaxCode;
+        if constexpr (PRUNE) prune_window<B, FMT>(v, lo_w, hi_w);
+
+        float w[8][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) w[0][j] = v[j];
+        for (int j = 0; j < 8; ++j) w[0][j] = v[j];
 #pragma unroll
-    for (int i = 1; i < 8; ++i) {
+        for (int i = 1; i < 8; ++i) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[i][j] = quot(v[j], Recip{mant_rhi(i), mant_rlo(i)});
+            for (int j = 0; j < 8; ++j) w[i][j] = quot(v[j], Recip{mant_rhi(i), mant_rlo(i)});
+        }
+
+        // sub-normal codes 1..7 = j * 2^(emin-3): 1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4
+        const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
+        const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
+        const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
+        if (lo_w < 8u) {                                                // uniform
+            GroupArgMin<B> g;
+            g.begin();
+            try_candidate<B, 0, 0>(v, w[0], s1, g);
+            try_candidate<B, 0, 1>(v, w[0], s2, g);
+            try_candidate<B, 4, 2>(v, w[4], s2, g);
+            try_candidate<B, 0, 3>(v, w[0], s4, g);
+            try_candidate<B, 2, 4>(v, w[2], s4, g);
+            try_candidate<B, 4, 5>(v, w[4], s4, g);
+            try_candidate<B, 6, 6>(v, w[6], s4, g);
+            g.end(st, 1u);
+        }
+
+        // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
+        for (uint32_t ef = max(lo_w >> 3, 1u); ef <= (hi_w >> 3); ++ef) {
+            const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
+            try_binade<B, FMT>(v, w, scale2, ef << 3, st);
+        }
+
+        // codes of the winners
+        float y[8];
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) {
+            S_best[k] = sf_decode<FMT>(st.best_code[k]);
+            const Recip r = make_recip(S_best[k]);
+#pragma unroll
+            for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
+        }
+        packed = e2m1_pack8(y, 1.0f);
     }
-#pragma unroll
-    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = 1u; }
+}
 
-    // sub-normal codes 1..7 = j * 2^(emin-3): 1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4
-    const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
-    const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
-    const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
-    if (lo_w < 8u) {                                                    // uniform
-        GroupArgMin<B> g;
-        g.begin();
-        try_candidate<B, 0, 0>(v, w[0], s1, g);
-        try_candidate<B, 0, 1>(v, w[0], s2, g);
-        try_candidate<B, 4, 2>(v, w[4], s2, g);
-        try_candidate<B, 0, 3>(v, w[0], s4, g);
-        try_candidate<B, 2, 4>(v, w[2], s4, g);
-        try_candidate<B, 4, 5>(v, w[4], s4, g);
-        try_candidate<B, 6, 6>(v, w[6], s4, g);
-        g.end(st, 1u);
-    }
-
-    // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
-    for (uint32_t ef = max(lo_w >> 3, 1u); ef <= (hi_w >> 3); ++ef) {
-        const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
-        try_binade<B, FMT>(v, w, scale2, ef << 3, st);
-    }
-
-    // codes of the winners
-    float y[8];
+// Clipping-only part of the winners' block SSE (appendix figure "Clipping only MSE"): elements with
+// |v| > 6 S quantise to +-6; their squared residuals, summed by the tree of the block SSE.
+template <int B>
+__device__ __forceinline__ void brute_clip_sse(const float (&v)[8], const float (&S)[BruteState<B>::NBLK], float (&clip)[4])
+{
+    constexpr int EPB = (B < 8) ? B : 8;
+    float sq[8];
 #pragma unroll
-    for (int k = 0; k < NBLK; ++k) {
-        const Recip r = make_recip(sf_decode<FMT>(st.best_code[k]));
-#pragma unroll
-        for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
+    for (int j = 0; j < 8; ++j) {
+        const float s = S[j / EPB];
+        const float q = u2f(0x40C00000u | (f2u(v[j]) & 0x80000000u));          // +-6
+        const float e = __builtin_fmaf(-q, s, v[j]);
+        sq[j] = (__builtin_fabsf(v[j]) > 6.0f * s) ? e * e : 0.0f;
     }
-    packed = e2m1_pack8(y, 1.0f);
+    const float p0 = sq[0] + sq[1], p1 = sq[2] + sq[3], p2 = sq[4] + sq[5], p3 = sq[6] + sq[7];
+    if constexpr (B == 2) { clip[0] = p0; clip[1] = p1; clip[2] = p2; clip[3] = p3; }
+    else if constexpr (B == 4) { clip[0] = p0 + p1; clip[1] = p2 + p3; }
+    else clip[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
 }
 
 template <int DT, int B, int FMT, bool HAS_T, bool PRUNE>
 __global__ void __launch_bounds__(kThreads)
 brute_kernel(const void* __restrict__ x, int64_t n_full, float T_arg,
              const float* __restrict__ absmax_dev, float* __restrict__ t_out,
-             uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+             uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out,
+             float* __restrict__ clip_out)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
@@ -297,7 +355,9 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T_arg,
         }
         uint32_t packed;
         BruteState<B> st;
-        brute_search<B, FMT, PRUNE>(v, packed, st);
+        float S_best[NBLK], clip[4];
+        brute_search<B, FMT, PRUNE>(v, packed, st, S_best);
+        if (clip_out) brute_clip_sse<B>(v, S_best, clip);               // uniform
 
         if (chunk < n_full) {
             codes[chunk] = packed;
@@ -306,6 +366,7 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T_arg,
                     const int64_t blk = chunk / LANES;
                     scales[blk] = (uint8_t)st.best_code[0];
                     if (sse_out) sse_out[blk] = st.best_sse[0];
+                    if (clip_out) clip_out[blk] = clip[0];
                 }
             } else {
                 const int64_t blk0 = chunk * NBLK;
@@ -313,6 +374,7 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T_arg,
                 for (int k = 0; k < NBLK; ++k) {
                     scales[blk0 + k] = (uint8_t)st.best_code[k];
                     if (sse_out) sse_out[blk0 + k] = st.best_sse[k];
+                    if (clip_out) clip_out[blk0 + k] = clip[k];
                 }
             }
         }
@@ -324,7 +386,8 @@ template <int DT, int B, int FMT, bool HAS_T, bool PRUNE>
 __global__ void __launch_bounds__(64)
 brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T_arg,
                   const float* __restrict__ absmax_dev, float* __restrict__ t_out,
-                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+                  uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out,
+                  float* __restrict__ clip_out)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     float T = T_arg;
@@ -342,13 +405,16 @@ brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T_
     }
     uint32_t packed;
     BruteState<B> st;
-    brute_search<B, FMT, PRUNE>(v, packed, st);
+    float S_best[NBLK], clip[4];
+    brute_search<B, FMT, PRUNE>(v, packed, st, S_best);
+    brute_clip_sse<B>(v, S_best, clip);
     if (threadIdx.x != 0) return;
     for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
     for (int k = 0; k < NBLK; ++k) {
         if (k < count / B) {
             scales[first / B + k] = (uint8_t)st.best_code[k];
             if (sse_out) sse_out[first / B + k] = st.best_sse[k];
+            if (clip_out) clip_out[first / B + k] = clip[k];
         }
     }
 }
@@ -364,10 +430,10 @@ static hipError_t launch_f(const StreamArgs& a)
         const dim3 grid((unsigned)(need < 256 * 8 ? need : 256 * 8)), block(kThreads);
         if (has_t)
             hipLaunchKernelGGL((brute_kernel<DT, B, FMT, true, PRUNE>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, a.absmax_dev, a.t_out, (uint32_t*)a.codes, a.scales, a.sse);
+                               a.x, n_full, a.T, a.absmax_dev, a.t_out, (uint32_t*)a.codes, a.scales, a.sse, a.clip);
         else
             hipLaunchKernelGGL((brute_kernel<DT, B, FMT, false, PRUNE>), grid, block, 0, a.stream,
-                               a.x, n_full, a.T, a.absmax_dev, a.t_out, (uint32_t*)a.codes, a.scales, a.sse);
+                               a.x, n_full, a.T, a.absmax_dev, a.t_out, (uint32_t*)a.codes, a.scales, a.sse, a.clip);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -376,10 +442,10 @@ static hipError_t launch_f(const StreamArgs& a)
             float* t_out_tail = (n_full > 0) ? nullptr : a.t_out;
             if (has_t)
                 hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, true, PRUNE>), dim3(1), dim3(64), 0, a.stream,
-                                   a.x, n_full * 8, count, a.T, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse);
+                                   a.x, n_full * 8, count, a.T, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse, a.clip);
             else
                 hipLaunchKernelGGL((brute_tail_kernel<DT, B, FMT, false, PRUNE>), dim3(1), dim3(64), 0, a.stream,
-                                   a.x, n_full * 8, count, a.T, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse);
+                                   a.x, n_full * 8, count, a.T, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse, a.clip);
         }
     }
     return hipGetLastError();
@@ -389,6 +455,7 @@ template <int DT, int B>
 static hipError_t launch_b(const StreamArgs& a)
 {
     const bool prune = (a.recipe == 5);
+    if (a.scale_fmt == kE8M0) return launch_f<DT, B, kE8M0, false>(a);          // the host refuses the pruned form
     if (a.scale_fmt == kE4M3) return prune ? launch_f<DT, B, kE4M3, true>(a) : launch_f<DT, B, kE4M3, false>(a);
     return prune ? launch_f<DT, B, kUE5M3, true>(a) : launch_f<DT, B, kUE5M3, false>(a);
 }

@@ -40,7 +40,7 @@ extern "C" {
 static int quantize_common(const void* x, int64_t rows, int64_t cols, int block,
                            int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
                            const float* absmax_dev, float* t_out,
-                           uint8_t* codes_out, uint8_t* scales_out, float* sse_out,
+                           uint8_t* codes_out, uint8_t* scales_out, float* sse_out, float* clip_out,
                            int x_dtype, void* stream)
 {
     if (rows < 0 || cols < 0) return MXQ_ERR_INVALID_ARG;
@@ -51,20 +51,22 @@ static int quantize_common(const void* x, int64_t rows, int64_t cols, int block,
     if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
     if (!(tensor_scale > 0.0f) || std::isinf(tensor_scale)) return MXQ_ERR_INVALID_ARG;
     if (rows > 0 && cols > INT64_MAX / rows) return MXQ_ERR_INVALID_ARG;
-    if (scale_fmt == MXQ_SCALE_E8M0 && recipe >= MXQ_RECIPE_4OVER6) return MXQ_ERR_UNSUPPORTED;
+    if (scale_fmt == MXQ_SCALE_E8M0 && recipe >= MXQ_RECIPE_4OVER6 && recipe != MXQ_RECIPE_BRUTE)
+        return MXQ_ERR_UNSUPPORTED;
     const int64_t n = rows * cols;
     if (n == 0) return MXQ_OK;
     if (n >= ((int64_t)1 << 42)) return MXQ_ERR_UNSUPPORTED;        // 32-bit slice counters
     if (!x || !codes_out || !scales_out) return MXQ_ERR_INVALID_ARG;
     if (!aligned(x, 16) || !aligned(codes_out, 4) || !aligned(scales_out, 4) ||
-        (sse_out && !aligned(sse_out, 16)) || !aligned(absmax_dev, 4) || !aligned(t_out, 4))
+        (sse_out && !aligned(sse_out, 16)) || (clip_out && !aligned(clip_out, 16)) ||
+        !aligned(absmax_dev, 4) || !aligned(t_out, 4))
         return MXQ_ERR_ALIGNMENT;
 
     mxq::StreamArgs a;
     a.x = x; a.n = n; a.dtype = x_dtype; a.block = block; a.scale_fmt = scale_fmt;
     a.recipe = recipe; a.T = tensor_scale; a.absmax_dev = absmax_dev; a.t_out = t_out;
     a.codes = codes_out; a.scales = scales_out;
-    a.sse = sse_out; a.stream = static_cast<hipStream_t>(stream);
+    a.sse = sse_out; a.clip = clip_out; a.stream = static_cast<hipStream_t>(stream);
     const hipError_t e = (recipe >= MXQ_RECIPE_BRUTE) ? mxq::launch_brute(a) : mxq::launch_stream(a);
     return e == hipSuccess ? MXQ_OK : MXQ_ERR_HIP;
 }
@@ -75,7 +77,16 @@ int mxq_quantize(const void* x, int64_t rows, int64_t cols, int block,
                  int x_dtype, void* stream)
 {
     return quantize_common(x, rows, cols, block, elem_fmt, scale_fmt, recipe, tensor_scale, nullptr, nullptr,
-                           codes_out, scales_out, sse_out, x_dtype, stream);
+                           codes_out, scales_out, sse_out, nullptr, x_dtype, stream);
+}
+
+int mxq_quantize_clip(const void* x, int64_t rows, int64_t cols, int block,
+                      int elem_fmt, int scale_fmt, int recipe, float tensor_scale,
+                      uint8_t* codes_out, uint8_t* scales_out, float* sse_out, float* clip_sse_out,
+                      int x_dtype, void* stream)
+{
+    return quantize_common(x, rows, cols, block, elem_fmt, scale_fmt, recipe, tensor_scale, nullptr, nullptr,
+                           codes_out, scales_out, sse_out, clip_sse_out, x_dtype, stream);
 }
 
 int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int block,
@@ -86,7 +97,7 @@ int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int block,
 {
     if (!absmax) return MXQ_ERR_INVALID_ARG;
     return quantize_common(x, rows, cols, block, elem_fmt, scale_fmt, recipe, 1.0f, absmax, tensor_scale_out,
-                           codes_out, scales_out, sse_out, x_dtype, stream);
+                           codes_out, scales_out, sse_out, nullptr, x_dtype, stream);
 }
 
 static int dequantize_common(const uint8_t* codes, const uint8_t* scales,

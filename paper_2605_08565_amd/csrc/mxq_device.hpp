@@ -132,6 +132,20 @@ __device__ __forceinline__ uint32_t e2m1_pack8(const float (&y)[8], float scale)
     return r;
 }
 
+// The same with one power-of-two scale per block of EPB elements inside the lane (EPB even, so
+// a pair never straddles two blocks).
+template <int EPB>
+__device__ __forceinline__ uint32_t e2m1_pack8_scales(const float (&y)[8], const float (&scale)[8 / EPB])
+{
+    uint32_t r;
+    asm volatile("" : "=v"(r));
+    r = e2m1_pack2<0>(r, y[0], y[1], scale[0 / EPB]);
+    r = e2m1_pack2<1>(r, y[2], y[3], scale[2 / EPB]);
+    r = e2m1_pack2<2>(r, y[4], y[5], scale[4 / EPB]);
+    r = e2m1_pack2<3>(r, y[6], y[7], scale[6 / EPB]);
+    return r;
+}
+
 __device__ __forceinline__ void e2m1_unpack8(uint32_t packed, float scale, float (&q)[8])
 {
     e2m1_unpack2<0>(packed, scale, q[0], q[1]);

@@ -19,6 +19,7 @@ struct StreamArgs {
     uint8_t* codes;
     uint8_t* scales;
     float* sse;
+    float* clip;               // device: clipping-only block SSE, or NULL
     hipStream_t stream;
 };
 

@@ -39,9 +39,9 @@ __device__ __forceinline__ void absmax_codes(float amax, uint32_t floor_code, ui
 // table scales: packed nibbles and the 8 squared residuals.
 template <int NBLK, int EPB>
 __device__ __forceinline__ void quant_lane(const float (&v)[8], const uint32_t (&code)[NBLK],
-                                           const ScaleEntry* tab, uint32_t& packed, float (&sq)[8])
+                                           const ScaleEntry* tab, uint32_t& packed, float (&sq)[8], float (&S)[NBLK])
 {
-    float y[8], S[NBLK];
+    float y[8];
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
         const ScaleEntry se = tab[code[k]];
@@ -62,45 +62,22 @@ __device__ __forceinline__ void quant_lane(const float (&v)[8], const uint32_t (
     }
 }
 
-// One block of EPB < 8 elements inside a lane under the power-of-two scale S: the byte
-// selector of the conversion must be a compile-time constant, hence the unrolled switch.
-template <int NBLK, int EPB>
-__device__ __forceinline__ void pow2_pairs(const float (&v)[8], float S, int k, uint32_t& packed, float (&sq)[8])
-{
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        if (p / (EPB / 2) != k) continue;
-        float q0 = 0.0f, q1 = 0.0f;
-        if (p == 0) { packed = e2m1_pack2<0>(packed, v[0], v[1], S); e2m1_unpack2<0>(packed, S, q0, q1); }
-        if (p == 1) { packed = e2m1_pack2<1>(packed, v[2], v[3], S); e2m1_unpack2<1>(packed, S, q0, q1); }
-        if (p == 2) { packed = e2m1_pack2<2>(packed, v[4], v[5], S); e2m1_unpack2<2>(packed, S, q0, q1); }
-        if (p == 3) { packed = e2m1_pack2<3>(packed, v[6], v[7], S); e2m1_unpack2<3>(packed, S, q0, q1); }
-        const float e0 = v[2 * p] - q0, e1 = v[2 * p + 1] - q1;
-        sq[2 * p] = e0 * e0;
-        sq[2 * p + 1] = e1 * e1;
-    }
-}
-
 // Same under power-of-two scales 2^(code-127): v / 2^k is exact, so the conversion
-// instruction applies the scale itself and the inverse conversion returns q * S.
+// instruction applies each block's scale itself and the inverse conversion returns q * S.
 template <int NBLK, int EPB>
 __device__ __forceinline__ void quant_lane_pow2(const float (&v)[8], const uint32_t (&code)[NBLK],
-                                                uint32_t& packed, float (&sq)[8])
+                                                uint32_t& packed, float (&sq)[8], float (&S)[NBLK])
 {
-    packed = 0u;
 #pragma unroll
-    for (int k = 0; k < NBLK; ++k) {
-        const float S = (code[k] == 0u) ? u2f(0x00400000u) : u2f(code[k] << 23);
-        if constexpr (NBLK == 1) {
-            packed = e2m1_pack8(v, S);
-            float qS[8];
-            e2m1_unpack8(packed, S, qS);
+    for (int k = 0; k < NBLK; ++k) S[k] = (code[k] == 0u) ? u2f(0x00400000u) : u2f(code[k] << 23);
+    packed = e2m1_pack8_scales<EPB>(v, S);
+    float qS[8];
+    e2m1_unpack2<0>(packed, S[0 / EPB], qS[0], qS[1]);
+    e2m1_unpack2<1>(packed, S[2 / EPB], qS[2], qS[3]);
+    e2m1_unpack2<2>(packed, S[4 / EPB], qS[4], qS[5]);
+    e2m1_unpack2<3>(packed, S[6 / EPB], qS[6], qS[7]);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { const float e = v[j] - qS[j]; sq[j] = e * e; }
-        } else {
-            pow2_pairs<NBLK, EPB>(v, S, k, packed, sq);
-        }
-    }
+    for (int j = 0; j < 8; ++j) { const float e = v[j] - qS[j]; sq[j] = e * e; }
 }
 
 // Block SSE: balanced tree in index order, inside the lane and then across the block's lanes.
@@ -116,6 +93,23 @@ __device__ __forceinline__ void block_sse(const float (&sq)[8], float (&sse)[4])
     } else {
         sse[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
     }
+}
+
+// Clipping-only part of the block SSE (appendix figure "Clipping only MSE"): the squared residuals
+// of the elements that saturate, |v| > 6 S (the same decision as fl32(|v| / S) > 6, because 6 S is
+// exact), others contribute +0; S = 0 clips nothing.  A saturating element quantises to +-6, so its
+// squared residual is the one the block SSE already holds.
+template <int B, int NBLK, int EPB>
+__device__ __forceinline__ void block_clip_sse(const float (&v)[8], const float (&sq)[8], const float (&S)[NBLK],
+                                               float (&clip)[4])
+{
+    float csq[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float s = S[j / EPB];
+        csq[j] = (__builtin_fabsf(v[j]) > 6.0f * s && s > 0.0f) ? sq[j] : 0.0f;
+    }
+    block_sse<B>(csq, clip);
 }
 
 // Division by the per-tensor scale T of hierarchical scaling: div_by_T (reciprocal + one FMA
@@ -166,10 +160,11 @@ __device__ __forceinline__ void adjust_and_amax(float (&v)[8], float T, float rT
 
 // Everything between the load and the store for one lane's 8 values.  `tdyn` (one of kNoT,
 // kFastT, kSlowT; wave-uniform) is read only when TMODE == kDynT.
-template <int B, int FMT, bool FOUR6, int TMODE>
+template <int B, int FMT, bool FOUR6, int TMODE, bool CLIP>
 __device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, int tdyn, bool pz,
                                               const ScaleEntry* tab, uint32_t& packed,
-                                              uint32_t (&code_out)[(B < 8) ? 8 / B : 1], float (&sse_sel)[4])
+                                              uint32_t (&code_out)[(B < 8) ? 8 / B : 1], float (&sse_sel)[4],
+                                              float (&clip_sel)[4])
 {
     constexpr int NBLK = (B < 8) ? 8 / B : 1;          // blocks inside one lane
     constexpr int LANES = (B < 8) ? 1 : B / 8;         // lanes per block
@@ -184,24 +179,27 @@ __device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, 
         adjust_and_amax<TMODE, NBLK, EPB, LANES>(v, T, rT, amax);
     }
 
-    float sq[8];
+    float sq[8], S[NBLK];
     if constexpr (FMT == kE8M0) {
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) code_out[k] = pow2_code(amax[k]);
-        quant_lane_pow2<NBLK, EPB>(v, code_out, packed, sq);
+        quant_lane_pow2<NBLK, EPB>(v, code_out, packed, sq, S);
         block_sse<B>(sq, sse_sel);
+        if constexpr (CLIP) block_clip_sse<B, NBLK, EPB>(v, sq, S, clip_sel);
     } else {
         uint32_t c4[NBLK];
         const uint32_t floor_code = pz ? 1u : 0u;
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) absmax_codes<FMT, FOUR6>(amax[k], floor_code, code_out[k], c4[k]);
-        quant_lane<NBLK, EPB>(v, code_out, tab, packed, sq);
+        quant_lane<NBLK, EPB>(v, code_out, tab, packed, sq, S);
         block_sse<B>(sq, sse_sel);
+        if constexpr (CLIP) block_clip_sse<B, NBLK, EPB>(v, sq, S, clip_sel);
         if constexpr (FOUR6) {
             uint32_t packed4;
-            float sse4[4];
-            quant_lane<NBLK, EPB>(v, c4, tab, packed4, sq);
+            float sse4[4], clip4[4];
+            quant_lane<NBLK, EPB>(v, c4, tab, packed4, sq, S);
             block_sse<B>(sq, sse4);
+            if constexpr (CLIP) block_clip_sse<B, NBLK, EPB>(v, sq, S, clip4);
             // Eq. 4: M = 4 only when its SSE is strictly lower
 #pragma unroll
             for (int k = 0; k < NBLK; ++k) {
@@ -211,6 +209,7 @@ __device__ __forceinline__ void process_chunk(float (&v)[8], float T, float rT, 
                     packed = (packed & ~mask) | (packed4 & mask);
                     code_out[k] = c4[k];
                     sse_sel[k] = sse4[k];
+                    if constexpr (CLIP) clip_sel[k] = clip4[k];
                 }
             }
         }
@@ -273,6 +272,7 @@ struct TileOut {
     uint32_t packed;
     uint32_t code[NBLK];
     float sse[4];
+    float clip[4];       // clipping-only SSE; carried only by the kernels that output it
 };
 
 // The complete chunks are cut into slices of 256 chunks (one chunk per lane).  Slice indices
@@ -288,7 +288,7 @@ struct Slices {
 template <int B>
 __device__ __forceinline__ void store_slice(const TileOut<B>& o, uint32_t s, Slices sl,
                                             uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
-                                            float* __restrict__ sse_out)
+                                            float* __restrict__ sse_out, float* __restrict__ clip_out)
 {
     constexpr int NBLK = TileOut<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
@@ -302,16 +302,21 @@ __device__ __forceinline__ void store_slice(const TileOut<B>& o, uint32_t s, Sli
                 const uint32_t blk = tid / LANES;
                 (scales + c0 / LANES)[blk] = (uint8_t)o.code[0];
                 if (sse_out) (sse_out + c0 / LANES)[blk] = o.sse[0];
+                if (clip_out) (clip_out + c0 / LANES)[blk] = o.clip[0];
             }
         } else if constexpr (NBLK == 2) {
             reinterpret_cast<uint16_t*>(scales + c0 * 2)[tid] = (uint16_t)(o.code[0] | (o.code[1] << 8));
             if (sse_out) reinterpret_cast<float2*>(sse_out + c0 * 2)[tid] = make_float2(o.sse[0], o.sse[1]);
+            if (clip_out) reinterpret_cast<float2*>(clip_out + c0 * 2)[tid] = make_float2(o.clip[0], o.clip[1]);
         } else {
             reinterpret_cast<uint32_t*>(scales + c0 * 4)[tid] =
                 o.code[0] | (o.code[1] << 8) | (o.code[2] << 16) | (o.code[3] << 24);
             if (sse_out)
                 reinterpret_cast<float4*>(sse_out + c0 * 4)[tid] =
                     make_float4(o.sse[0], o.sse[1], o.sse[2], o.sse[3]);
+            if (clip_out)
+                reinterpret_cast<float4*>(clip_out + c0 * 4)[tid] =
+                    make_float4(o.clip[0], o.clip[1], o.clip[2], o.clip[3]);
         }
     }
 }
@@ -340,13 +345,13 @@ __device__ __forceinline__ void load_tile(RawChunk<DT> (&buf)[kItems], const voi
 // On gfx9 loads and stores share one in-order counter, so the wait at the top covers every
 // memory operation still in flight; with this order all of them were issued a whole compute
 // phase earlier and the wait is short.
-template <int DT, int B, int FMT, bool FOUR6, int TMODE>
+template <int DT, int B, int FMT, bool FOUR6, int TMODE, bool CLIP>
 __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChunk<DT> (&nxt)[kItems],
                                             TileOut<B> (&out)[kItems], bool have_prev, uint32_t s_prev,
                                             const void* __restrict__ x, uint32_t s0, uint32_t stride,
                                             Slices sl, float T, float rT, int tdyn, bool pz, const ScaleEntry* tab,
                                             u32x4* wave_lds, uint32_t* __restrict__ codes, uint8_t* __restrict__ scales,
-                                            float* __restrict__ sse_out)
+                                            float* __restrict__ sse_out, float* __restrict__ clip_out)
 {
     float v[kItems][8];
     __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0)
@@ -355,22 +360,25 @@ __device__ __forceinline__ void stream_step(RawChunk<DT> (&cur)[kItems], RawChun
     __builtin_amdgcn_sched_barrier(0);
     if (have_prev) {                                                 // uniform
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out);
+        for (int i = 0; i < kItems; ++i)
+            store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out, CLIP ? clip_out : nullptr);
     }
     if (s0 + stride < sl.count) load_tile<DT>(nxt, x, s0 + stride, sl);            // uniform
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kItems; ++i)
-        process_chunk<B, FMT, FOUR6, TMODE>(v[i], T, rT, tdyn, pz, tab, out[i].packed, out[i].code, out[i].sse);
+        process_chunk<B, FMT, FOUR6, TMODE, CLIP>(v[i], T, rT, tdyn, pz, tab, out[i].packed, out[i].code, out[i].sse,
+                                                  out[i].clip);
 }
 
 // Main kernel: the complete chunks, grid-stride over workgroup tiles with two register buffers
 // alternating between "being processed" and "in flight".
-template <int DT, int B, int FMT, bool FOUR6, int TMODE>
+template <int DT, int B, int FMT, bool FOUR6, int TMODE, bool CLIP>
 __global__ void __launch_bounds__(kThreads)
 stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunks, float T_arg, int pz,
               const float* __restrict__ absmax_dev, float* __restrict__ t_out,
-              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+              uint32_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out,
+              float* __restrict__ clip_out)
 {
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
     __shared__ u32x4 xpose[(DT == kF32) ? 2 * kThreads : 1];        // 2 KiB per wavefront, fp32 input only
@@ -382,8 +390,8 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
     if (s0 >= sl.count) return;                                      // whole workgroup
     float T = T_arg;
     int tdyn = TMODE;
-    if constexpr (TMODE == kDynT) {                                  // T from the abs-max left in device memory
-        T = tensor_scale_of<FMT>(*absmax_dev);
+    if constexpr (TMODE == kDynT) {                  // T from the abs-max left in device memory, if there is one
+        if (absmax_dev) T = tensor_scale_of<FMT>(*absmax_dev);
         tdyn = (T == 1.0f) ? kNoT : (fast_division_ok(T) ? kFastT : kSlowT);
         if (t_out && blockIdx.x == 0 && threadIdx.x == 0) *t_out = T;
     }
@@ -399,20 +407,21 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
     bool have_prev = false;
     uint32_t s_prev = s0;
     while (true) {
-        stream_step<DT, B, FMT, FOUR6, TMODE>(bufA, bufB, out, have_prev, s_prev, x, s0, stride, sl,
-                                              T, rT, tdyn, pz != 0, tab, wave_lds, codes, scales, sse_out);
+        stream_step<DT, B, FMT, FOUR6, TMODE, CLIP>(bufA, bufB, out, have_prev, s_prev, x, s0, stride, sl, T, rT, tdyn,
+                                                    pz != 0, tab, wave_lds, codes, scales, sse_out, clip_out);
         have_prev = true;
         s_prev = s0;
         s0 += stride;
         if (s0 >= sl.count) break;
-        stream_step<DT, B, FMT, FOUR6, TMODE>(bufB, bufA, out, true, s_prev, x, s0, stride, sl,
-                                              T, rT, tdyn, pz != 0, tab, wave_lds, codes, scales, sse_out);
+        stream_step<DT, B, FMT, FOUR6, TMODE, CLIP>(bufB, bufA, out, true, s_prev, x, s0, stride, sl, T, rT, tdyn,
+                                                    pz != 0, tab, wave_lds, codes, scales, sse_out, clip_out);
         s_prev = s0;
         s0 += stride;
         if (s0 >= sl.count) break;
     }
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out);
+    for (int i = 0; i < kItems; ++i)
+        store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out, CLIP ? clip_out : nullptr);
 }
 
 // Ragged tail: when n is not a multiple of 8 (only possible for b = 2 or 4) the last
@@ -421,23 +430,24 @@ template <int DT, int B, int FMT, bool FOUR6, int TMODE>
 __global__ void __launch_bounds__(64)
 stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T_arg, int pz,
                    const float* __restrict__ absmax_dev, float* __restrict__ t_out,
-                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out)
+                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, float* __restrict__ sse_out,
+                   float* __restrict__ clip_out)
 {
     constexpr int NBLK = (B < 8) ? 8 / B : 1;
     __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
     if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
 
-    float v[8], sse_sel[4];
+    float v[8], sse_sel[4], clip_sel[4];
     uint32_t packed, code_out[NBLK];
     load_partial<DT>(x, first, (threadIdx.x == 0) ? count : 0, v);
     float T = T_arg;
     int tdyn = TMODE;
     if constexpr (TMODE == kDynT) {
-        T = tensor_scale_of<FMT>(*absmax_dev);
+        if (absmax_dev) T = tensor_scale_of<FMT>(*absmax_dev);
         tdyn = (T == 1.0f) ? kNoT : kSlowT;
         if (t_out && threadIdx.x == 0) *t_out = T;      // t_out is passed only when no main kernel runs
     }
-    process_chunk<B, FMT, FOUR6, TMODE>(v, T, 1.0f / T, tdyn, pz != 0, tab, packed, code_out, sse_sel);
+    process_chunk<B, FMT, FOUR6, TMODE, true>(v, T, 1.0f / T, tdyn, pz != 0, tab, packed, code_out, sse_sel, clip_sel);
     if (threadIdx.x != 0) return;
     for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
     if constexpr (B < 8) {
@@ -445,6 +455,7 @@ stream_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T
             if (k < count / B) {
                 scales[first / B + k] = (uint8_t)code_out[k];
                 if (sse_out) sse_out[first / B + k] = sse_sel[k];
+                if (clip_out) clip_out[first / B + k] = clip_sel[k];
             }
         }
     }
@@ -459,20 +470,22 @@ static hipError_t launch_recipe(const StreamArgs& a, int pz)
     const int count = (int)(a.n - n_full * 8);
     // reciprocal-refined division only where its exactness argument holds; with the abs-max in
     // device memory the kernel makes the same choice itself
-    const int tmode = a.absmax_dev ? kDynT : (a.T == 1.0f) ? kNoT : (fast_division_ok(a.T) ? kFastT : kSlowT);
+    // the variant that also writes the clipping-only SSE exists for the run-time mode only
+    const int tmode = (a.absmax_dev || a.clip) ? kDynT : (a.T == 1.0f) ? kNoT : (fast_division_ok(a.T) ? kFastT : kSlowT);
     if (n_full > 0) {
         const int64_t slices = (n_full + kThreads - 1) / kThreads;
         const uint32_t n_slices = (uint32_t)slices;
         const uint32_t last = (uint32_t)(n_full - (slices - 1) * kThreads);
         const dim3 grid(stream_grid(((slices + kItems - 1) / kItems) * kThreads)), block(kThreads);
         uint32_t* codes = reinterpret_cast<uint32_t*>(a.codes);
-#define MXQ_LAUNCH_STREAM(MODE)                                                                       \
-    hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, MODE>), grid, block, 0, a.stream, a.x, n_slices,    \
-                       last, a.T, pz, a.absmax_dev, a.t_out, codes, a.scales, a.sse)
-        if (tmode == kNoT) MXQ_LAUNCH_STREAM(kNoT);
-        else if (tmode == kFastT) MXQ_LAUNCH_STREAM(kFastT);
-        else if (tmode == kSlowT) MXQ_LAUNCH_STREAM(kSlowT);
-        else MXQ_LAUNCH_STREAM(kDynT);
+#define MXQ_LAUNCH_STREAM(MODE, CLIP)                                                                 \
+    hipLaunchKernelGGL((stream_kernel<DT, B, FMT, FOUR6, MODE, CLIP>), grid, block, 0, a.stream, a.x,       \
+                       n_slices, last, a.T, pz, a.absmax_dev, a.t_out, codes, a.scales, a.sse, a.clip)
+        if (a.clip) MXQ_LAUNCH_STREAM(kDynT, true);
+        else if (tmode == kNoT) MXQ_LAUNCH_STREAM(kNoT, false);
+        else if (tmode == kFastT) MXQ_LAUNCH_STREAM(kFastT, false);
+        else if (tmode == kSlowT) MXQ_LAUNCH_STREAM(kSlowT, false);
+        else MXQ_LAUNCH_STREAM(kDynT, false);
 #undef MXQ_LAUNCH_STREAM
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -482,7 +495,7 @@ static hipError_t launch_recipe(const StreamArgs& a, int pz)
             float* t_out_tail = (n_full > 0) ? nullptr : a.t_out;
 #define MXQ_LAUNCH_TAIL(MODE)                                                                         \
     hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, MODE>), dim3(1), dim3(64), 0, a.stream, a.x,   \
-                       n_full * 8, count, a.T, pz, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse)
+                       n_full * 8, count, a.T, pz, a.absmax_dev, t_out_tail, a.codes, a.scales, a.sse, a.clip)
             if (tmode == kDynT) MXQ_LAUNCH_TAIL(kDynT);
             else if (tmode != kNoT) MXQ_LAUNCH_TAIL(kSlowT);
             else MXQ_LAUNCH_TAIL(kNoT);

@@ -41,6 +41,8 @@ def lib() -> ctypes.CDLL:
     i64, i32, f32, vp, u8 = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_uint8
     L.mxq_quantize.restype = i32
     L.mxq_quantize.argtypes = [vp, i64, i64, i32, i32, i32, i32, f32, vp, vp, vp, i32, vp]
+    L.mxq_quantize_clip.restype = i32
+    L.mxq_quantize_clip.argtypes = [vp, i64, i64, i32, i32, i32, i32, f32, vp, vp, vp, vp, i32, vp]
     L.mxq_quantize_hier.restype = i32
     L.mxq_quantize_hier.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
     L.mxq_dequantize.restype = i32
@@ -112,8 +114,9 @@ def _nblocks(rows: int, cols: int, block: int) -> int:
 def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_scale: float = 1.0,
              codes_out: torch.Tensor | None = None, scales_out: torch.Tensor | None = None,
              sse_out: torch.Tensor | None = None, want_sse: bool = True, stream=None,
-             elem_fmt: int = ELEM_E2M1):
-    """mxq_quantize on a 2-D contiguous CUDA tensor. Returns (codes, scales, sse)."""
+             elem_fmt: int = ELEM_E2M1, clip_sse_out: torch.Tensor | None = None):
+    """mxq_quantize on a 2-D contiguous CUDA tensor. Returns (codes, scales, sse).  With
+    `clip_sse_out` (fp32 [rows, cols/block]) mxq_quantize_clip, which also fills that tensor."""
     if not x.is_cuda or x.dim() != 2 or not x.is_contiguous():
         raise ValueError("x must be a contiguous 2-D tensor on the GPU")
     rows, cols = x.shape
@@ -128,6 +131,13 @@ def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_sc
     _need(scales_out, _nblocks(rows, cols, block), "scales_out", torch.uint8)
     if sse_out is not None:
         _need(sse_out, 4 * _nblocks(rows, cols, block), "sse_out", torch.float32)
+    if clip_sse_out is not None:
+        _need(clip_sse_out, 4 * _nblocks(rows, cols, block), "clip_sse_out", torch.float32)
+        _check(lib().mxq_quantize_clip(x.data_ptr(), rows, cols, block, elem_fmt, scale_fmt, recipe,
+                                       float(tensor_scale), codes_out.data_ptr(), scales_out.data_ptr(),
+                                       sse_out.data_ptr() if sse_out is not None else None,
+                                       clip_sse_out.data_ptr(), _dtype_code(x), _stream_ptr(stream)))
+        return codes_out, scales_out, sse_out
     _check(lib().mxq_quantize(x.data_ptr(), rows, cols, block, elem_fmt, scale_fmt, recipe,
                               float(tensor_scale), codes_out.data_ptr(), scales_out.data_ptr(),
                               sse_out.data_ptr() if sse_out is not None else None,
@@ -265,13 +275,19 @@ def clip_sse(x: torch.Tensor, scales: torch.Tensor, block: int, scale_fmt: int,
 
 
 def histogram(codes: torch.Tensor, scales: torch.Tensor, block: int, stream=None,
-              elem_fmt: int = ELEM_E2M1):
-    """mxq_histogram: (int64 [8] magnitude-index counts, int64 [256] scale-byte counts)."""
+              elem_fmt: int = ELEM_E2M1, out=None):
+    """mxq_histogram: (int64 [8] magnitude-index counts, int64 [256] scale-byte counts); `out` may
+    hold the two result tensors."""
     rows, half = codes.shape
     _need(codes, rows * half, "codes", torch.uint8)
     _need(scales, _nblocks(rows, half * 2, block), "scales", torch.uint8)
-    eh = torch.empty(8, dtype=torch.int64, device=codes.device)
-    sh = torch.empty(256, dtype=torch.int64, device=codes.device)
+    if out is not None:
+        eh, sh = out
+        _need(eh, 64, "out[0]", torch.int64)
+        _need(sh, 2048, "out[1]", torch.int64)
+    else:
+        eh = torch.empty(8, dtype=torch.int64, device=codes.device)
+        sh = torch.empty(256, dtype=torch.int64, device=codes.device)
     _check(lib().mxq_histogram(codes.data_ptr(), scales.data_ptr(), rows, half * 2, block, elem_fmt,
                                eh.data_ptr(), sh.data_ptr(), _stream_ptr(stream)))
     return eh, sh

@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc", "mxq_tensor_absmax_static",
+    assert names == sorted(["mxq_quantize", "mxq_quantize_clip", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc", "mxq_tensor_absmax_static",
                             "mxq_tensor_absmax_workspace_size", "mxq_clip_sse",
                             "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
@@ -76,7 +76,7 @@ def test_argument_validation_without_a_launch(mxq):
     for T in (0.0, -1.0, float("inf"), float("nan")):
         assert q(T=T) == mxq.ERR_INVALID_ARG
     assert q(fmt=0, rec=2) == mxq.ERR_UNSUPPORTED
-    assert q(fmt=0, rec=4) == mxq.ERR_UNSUPPORTED
+    assert q(fmt=0, rec=3) == mxq.ERR_UNSUPPORTED
     assert q(fmt=0, rec=5) == mxq.ERR_UNSUPPORTED
     assert q(x=P + 2) == mxq.ERR_ALIGNMENT
     assert q(codes=P + 1) == mxq.ERR_ALIGNMENT
@@ -89,12 +89,19 @@ def test_argument_validation_without_a_launch(mxq):
     assert q(rows=0, x=None, codes=None, scales=None, sse=None) == mxq.OK
     assert q(rows=3, cols=0) == mxq.OK
 
+    def qc(x=P, rows=4, cols=64, block=16, elem=0, fmt=1, rec=0, T=1.0, codes=P, scales=P, sse=P, clip=P, dt=0):
+        return L.mxq_quantize_clip(x, rows, cols, block, elem, fmt, rec, T, codes, scales, sse, clip, dt, None)
+
+    assert qc(x=None) == mxq.ERR_INVALID_ARG and qc(block=3) == mxq.ERR_INVALID_ARG
+    assert qc(clip=P + 4) == mxq.ERR_ALIGNMENT and qc(sse=P + 8) == mxq.ERR_ALIGNMENT
+    assert qc(fmt=0, rec=2) == mxq.ERR_UNSUPPORTED and qc(rows=0) == mxq.OK
+
     def qh(x=P, rows=4, cols=64, block=16, elem=0, fmt=1, rec=0, amax=P, t_out=P, codes=P, scales=P, sse=P, dt=0):
         return L.mxq_quantize_hier(x, rows, cols, block, elem, fmt, rec, amax, t_out, codes, scales, sse, dt, None)
 
     assert qh(amax=None) == mxq.ERR_INVALID_ARG
     assert qh(x=None) == mxq.ERR_INVALID_ARG and qh(block=3) == mxq.ERR_INVALID_ARG
-    assert qh(fmt=0, rec=4) == mxq.ERR_UNSUPPORTED
+    assert qh(fmt=0, rec=5) == mxq.ERR_UNSUPPORTED
     assert qh(amax=P + 2) == mxq.ERR_ALIGNMENT and qh(t_out=P + 1) == mxq.ERR_ALIGNMENT
     assert qh(rows=0) == mxq.OK and qh(rows=0, t_out=None) == mxq.OK
 

@@ -28,7 +28,7 @@ def mxq():
 
 
 def combos(brute=True):
-    out = [(0, 0)]
+    out = [(0, 0)] + ([(0, 4)] if brute else [])
     for fmt in (1, 2):
         for rec in (0, 1, 2, 3) + ((4, 5) if brute else ()):
             out.append((fmt, rec))
@@ -50,6 +50,15 @@ def check(oracle, mxq, x_np, block, fmt, rec, T=1.0, tag=""):
     assert (gs == os_).all(), f"scale bytes differ in {(gs != os_).sum()} blocks"
     assert (gc == oc).all(), f"code bytes differ in {(gc != oc).sum()} bytes"
     assert (ge.view(np.uint32) == oe.view(np.uint32)).all(), "block SSE not bit-identical"
+    if x_np.size:            # the same call with the clipping-only SSE as a fourth output
+        x = mxq.from_bits(x_np)
+        clip = torch.full((x_np.shape[0], x_np.shape[1] // block), -1.0, dtype=torch.float32, device="cuda")
+        c2, s2, e2 = mxq.quantize(x, block, fmt, rec, tensor_scale=T, clip_sse_out=clip)
+        torch.cuda.synchronize()
+        assert (c2.cpu().numpy() == oc).all() and (s2.cpu().numpy() == os_).all()
+        assert (e2.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all()
+        want = oracle.clip_sse(x_np, os_, block, fmt, tensor_scale=T)
+        assert (clip.cpu().numpy().view(np.uint32) == want.view(np.uint32)).all(), "clipping-only SSE differs"
     if x_np.size:
         m_g, m_o = oracle.tensor_mse(ge, x_np.size, T), oracle.tensor_mse(oe, x_np.size, T)
         if np.isfinite(m_o):
@@ -457,6 +466,17 @@ def test_config2_full_size(oracle, mxq):
             check_full(oracle, x_np, outs[rec], block, 1, rec)
         assert bool((outs[0][2] >= outs[2][2]).all())
         assert bool((outs[0][2] >= outs[1][2]).all())
+    # the fused clipping-only SSE at full size: equal to the separate pass on the same scales and
+    # to the oracle's, for abs-max and for 4-over-6
+    for block, rec in ((16, 0), (16, 2), (64, 2), (8, 1)):
+        print(f"[parity] config2 fused clip b={block} recipe={REC_NAMES[rec]}", flush=True)
+        clip = torch.empty((x_np.shape[0], x_np.shape[1] // block), dtype=torch.float32, device="cuda")
+        c, s, e = mxq.quantize(x, block, 1, rec, clip_sse_out=clip)
+        sep = mxq.clip_sse(x, s, block, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(clip.view(torch.int32), sep.view(torch.int32))
+        want = oracle.clip_sse(x_np, s.cpu().numpy(), block, 1)
+        assert (clip.cpu().numpy().view(np.uint32) == want.view(np.uint32)).all()
 
 
 def test_config3_full_size(oracle, mxq):
@@ -498,6 +518,22 @@ def test_config4_brute_full_size(oracle, mxq, fmt, block):
     pr = mxq.quantize(x, block, fmt, 5)
     torch.cuda.synchronize()
     assert all(torch.equal(a, b) for a, b in zip(out, pr))
+
+
+def test_brute_force_over_power_of_two_scales_full_size(oracle, mxq):
+    """The search over all 255 power-of-two scales on the full 4096 x 14336 weights (b = 32, the
+    MX block size): 1 024 whole rows against the oracle; on every block its SSE is at most that of
+    the floor rule of Eq. 1, which is one of its candidates."""
+    x_np = W.config2()
+    x = mxq.from_bits(x_np)
+    for block in (32, 4):
+        out = mxq.quantize(x, block, 0, 4)
+        floor_rule = mxq.quantize(x, block, 0, 0)
+        torch.cuda.synchronize()
+        assert bool((out[2] <= floor_rule[2]).all())
+        rows = sample_rows(x_np.shape[0], 1024 if block == 32 else 256, seed=44)
+        print(f"[parity] e8m0 brute b={block} rows={len(rows)}", flush=True)
+        check_rows(oracle, x_np, rows, out, block, 0, 4)
 
 
 def test_config5_layer0(oracle, mxq):
