@@ -106,6 +106,10 @@ def extra_passes():
             p.append(("a3", "quant", f"config3_{REC[r]}_e4m3_b{b}_H_quantise_only", b, E4M3, r, True))
             for mode in ("cold", "warm"):
                 p.append(("a3", "two_pass_" + mode, f"config3_absmax_then_{REC[r]}_e4m3_b{b}_H_{mode}", b, E4M3, r, True))
+    # the search on activations (blocks of very different magnitude share a wavefront)
+    for b in (16, 4):
+        p.append(("a3", "quant", f"config3_brute_e4m3_b{b}_H", b, E4M3, BRUTE, True))
+        p.append(("a3", "quant", f"config3_brute_pruned_e4m3_b{b}_H", b, E4M3, BRUTE_PRUNED, True))
     return p
 
 
@@ -447,7 +451,7 @@ def main():
         if kind in ("dequant", "dequant_f32", "clip", "hist"):
             need_dq(wl)
         warm = kind == "two_pass_warm"
-        hmode = "device" if (hier and tag == "a3" and kind == "quant") else hier
+        hmode = "device" if (hier and tag == "a3" and kind == "quant" and rec < BRUTE) else hier
         if hmode == "device":                     # the quantise pass alone needs a valid abs-max per set
             for k in range(wl.n_sets):
                 wl.amax[k:k + 1].zero_()

@@ -59,7 +59,19 @@ struct GroupArgMin {
     }
     template <int POS>
     __device__ __forceinline__ void put(int k, float sse) { s[k][POS] = sse; }
+    // Take position 7 of block slot k out of this group (the code there is not a number).
+    __device__ __forceinline__ void drop_last(int k, bool drop) { s[k][7] = drop ? __builtin_inff() : s[k][7]; }
+
     __device__ __forceinline__ void end(BruteState<B>& st, uint32_t code0) const
+    {
+        uint32_t c0[NBLK];
+        bool ok[NBLK];
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) { c0[k] = code0; ok[k] = true; }
+        end(st, c0, ok);
+    }
+    // code0 per block slot; a slot with ok == false takes no part in this group
+    __device__ __forceinline__ void end(BruteState<B>& st, const uint32_t (&code0)[NBLK], const bool (&ok)[NBLK]) const
     {
         float gmin[NBLK];
         bool any = false;
@@ -68,7 +80,7 @@ struct GroupArgMin {
             const float a = fminf(fminf(s[k][0], s[k][1]), s[k][2]);
             const float b = fminf(fminf(s[k][3], s[k][4]), s[k][5]);
             gmin[k] = fminf(fminf(a, b), fminf(s[k][6], s[k][7]));
-            any |= gmin[k] < st.best_sse[k];
+            any |= ok[k] && gmin[k] < st.best_sse[k];
         }
         if (__builtin_amdgcn_ballot_w64(any) == 0ull) return;           // wave-uniform
 #pragma unroll
@@ -76,8 +88,8 @@ struct GroupArgMin {
             uint32_t pos = 7u;
 #pragma unroll
             for (int i = 6; i >= 0; --i) pos = (s[k][i] == gmin[k]) ? (uint32_t)i : pos;
-            const bool better = gmin[k] < st.best_sse[k];
-            st.best_code[k] = better ? code0 + pos : st.best_code[k];
+            const bool better = ok[k] && gmin[k] < st.best_sse[k];
+            st.best_code[k] = better ? code0[k] + pos : st.best_code[k];
             st.best_sse[k] = better ? gmin[k] : st.best_sse[k];
         }
     }
@@ -107,6 +119,9 @@ __device__ __forceinline__ void try_candidate(const float (&v)[8], const float (
     } else {
         g.template put<POS>(0, group_sum<B / 8>((p0 + p1) + (p2 + p3)));
     }
+    // One candidate at a time: left alone, the instruction scheduler interleaves several
+    // candidates, which costs registers and 10 % of the kernel's speed (measured).
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int B, int FMT, int MI, class G>
@@ -143,8 +158,19 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 //        is a lower bound of the candidate's SSE.  Once it exceeds U, the SSE of a reference
 //        candidate (the abs-max scale), the candidate cannot win; the bound falls with S, so
 //        the losers form a prefix of the code range, found by bisection.
-// The scan stays wave-uniform: the wavefront visits the union of its blocks' windows, widened
-// to whole binades.
+// Windows of different blocks sit at different places of the code range (wherever the block's
+// abs-max puts them) but have nearly the same width, about one binade below the abs-max scale to
+// five above.  So the scan is wave-uniform in RELATIVE terms: in step d every block tries the
+// binade d above the binade of its own abs-max scale (the power of two handed to the conversion
+// instruction is a per-lane register, the mantissa stays uniform), d running over the union of
+// the relative windows.  A wavefront with 128 small blocks then visits hardly more candidates
+// than one block alone would, where a scan of the union of the absolute windows degraded with
+// the number of blocks per wavefront.  Lanes whose step falls outside the format's code range
+// are masked out; the sub-normal codes are one uniform group in front.  Every block still
+// visits a superset of its own window, in ascending code order.  When the blocks of a wavefront
+// are alike (weights), the union of the absolute windows is no wider than the relative one and
+// its scan is a few percent cheaper (uniform scale operand), so each wavefront takes whichever
+// of the two scans has fewer steps.
 // ---------------------------------------------------------------------------------------
 template <int FMT>
 __device__ __forceinline__ uint32_t ceil_code(float y)      // smallest code >= 1 with value >= y
@@ -154,8 +180,11 @@ __device__ __forceinline__ uint32_t ceil_code(float y)      // smallest code >= 
     return max(c, 1u);
 }
 
+// Per block of the lane: binade (exponent field) of the abs-max scale, and the window [lo, hi] of
+// codes that can win.
 template <int B, int FMT>
-__device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t& lo_w, uint32_t& hi_w)
+__device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&eref)[BruteState<B>::NBLK],
+                                             uint32_t (&lo_k)[BruteState<B>::NBLK], uint32_t (&hi_k)[BruteState<B>::NBLK])
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
@@ -184,7 +213,6 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t& lo_w
     else if constexpr (B == 4) { U[0] = p0 + p1; U[1] = p2 + p3; }
     else U[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
 
-    uint32_t lo_all = 0xFFFFFFFFu, hi_all = 0u;
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
         uint32_t lo = 1u, hi = cref[k];                 // the bound at cref is <= U: not a loser
@@ -198,16 +226,51 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t& lo_w
                 if (loser) lo = mid + 1u; else hi = mid;
             }
         }
-        lo_all = min(lo_all, lo);
-        hi_all = max(hi_all, ceil_code<FMT>(4.0f * amax[k]));
+        lo_k[k] = lo;
+        hi_k[k] = ceil_code<FMT>(4.0f * amax[k]);
+        eref[k] = cref[k] >> 3;
     }
+}
+
+// One candidate of the relative scan: mantissa MI (uniform), power of two per block.
+template <int B, int MI, int POS, class G>
+__device__ __forceinline__ void try_candidate_rel(const float (&v)[8], const float (&w)[8],
+                                                  const float (&scale2)[BruteState<B>::NBLK], G& g)
+{
+    constexpr int EPB = (B < 8) ? B : 8;
+    const uint32_t packed = e2m1_pack8_scales<EPB>(w, scale2);
+    float q2[8], sq[8];
+    e2m1_unpack2<0>(packed, scale2[0 / EPB], q2[0], q2[1]);
+    e2m1_unpack2<1>(packed, scale2[2 / EPB], q2[2], q2[3]);
+    e2m1_unpack2<2>(packed, scale2[4 / EPB], q2[4], q2[5]);
+    e2m1_unpack2<3>(packed, scale2[6 / EPB], q2[6], q2[7]);
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        lo_all = min(lo_all, (uint32_t)__shfl_xor((int)lo_all, off, 64));
-        hi_all = max(hi_all, (uint32_t)__shfl_xor((int)hi_all, off, 64));
+    for (int j = 0; j < 8; ++j) {
+        float e;
+        if constexpr (MI == 0) e = v[j] - q2[j];
+        else e = __builtin_fmaf(-q2[j], mant_value(MI), v[j]);
+        sq[j] = e * e;
     }
-    lo_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)lo_all);
-    hi_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)hi_all);
+    const float p0 = sq[0] + sq[1], p1 = sq[2] + sq[3], p2 = sq[4] + sq[5], p3 = sq[6] + sq[7];
+    if constexpr (B == 2) {
+        g.template put<POS>(0, p0); g.template put<POS>(1, p1);
+        g.template put<POS>(2, p2); g.template put<POS>(3, p3);
+    } else if constexpr (B == 4) {
+        g.template put<POS>(0, p0 + p1); g.template put<POS>(1, p2 + p3);
+    } else {
+        g.template put<POS>(0, group_sum<B / 8>((p0 + p1) + (p2 + p3)));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int B, int MI, class G>
+__device__ __forceinline__ void try_binade_rel_from(const float (&v)[8], const float (&w)[8][8],
+                                                    const float (&scale2)[BruteState<B>::NBLK], G& g)
+{
+    if constexpr (MI < 8) {
+        try_candidate_rel<B, MI, MI>(v, w[MI], scale2, g);
+        try_binade_rel_from<B, MI + 1>(v, w, scale2, g);
+    }
 }
 
 // Value of a power-of-two scale byte (0 .. 254); 2^-127 is a sub-normal float.
@@ -226,79 +289,192 @@ __device__ __forceinline__ void try_pow2_from(const float (&v)[8], uint32_t code
     }
 }
 
-// Search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE, and
-// the scale value of every winner.
+// Search for the lane's 8 values (already divided by T): winner codes, packed nibbles, SSE.
 template <int B, int FMT, bool PRUNE>
-__device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& packed, BruteState<B>& st,
-                                             float (&S_best)[BruteState<B>::NBLK])
+__device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
+{
+    constexpr int NBLK = BruteState<B>::NBLK;
+    constexpr int EPB = (B < 8) ? B : 8;
+    constexpr int bias = ScaleFmt<FMT>::kBias;
+    constexpr int emin = 1 - bias;                                      // exponent of the first binade
+
+    constexpr uint32_t lo_w = 1u, hi_w = (uint32_t)ScaleFmt<FMT>::kMaxCode;
+    static_assert(!PRUNE, "the pruned search is brute_search_pruned");
+
+    float w[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[0][j] = v[j];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[i][j] = quot(v[j], Recip{mant_rhi(i), mant_rlo(i)});
+    }
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = 1u; }
+
+    // sub-normal codes 1..7 = j * 2^(emin-3): 1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4
+    const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
+    const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
+    const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
+    if (lo_w < 8u) {                                                    // uniform
+        GroupArgMin<B> g;
+        g.begin();
+        try_candidate<B, 0, 0>(v, w[0], s1, g);
+        try_candidate<B, 0, 1>(v, w[0], s2, g);
+        try_candidate<B, 4, 2>(v, w[4], s2, g);
+        try_candidate<B, 0, 3>(v, w[0], s4, g);
+        try_candidate<B, 2, 4>(v, w[2], s4, g);
+        try_candidate<B, 4, 5>(v, w[4], s4, g);
+        try_candidate<B, 6, 6>(v, w[6], s4, g);
+        g.end(st, 1u);
+    }
+
+    // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
+    for (uint32_t ef = max(lo_w >> 3, 1u); ef <= (hi_w >> 3); ++ef) {
+        const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
+        try_binade<B, FMT>(v, w, scale2, ef << 3, st);
+    }
+
+    // codes of the winners
+    float y[8];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        const Recip r = make_recip(sf_decode<FMT>(st.best_code[k]));
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
+    }
+    packed = e2m1_pack8(y, 1.0f);
+}
+
+// Pruned search: the relative scan described above.
+template <int B, int FMT>
+__device__ __forceinline__ void brute_search_pruned(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
+{
+    constexpr int NBLK = BruteState<B>::NBLK;
+    constexpr int EPB = (B < 8) ? B : 8;
+    constexpr int bias = ScaleFmt<FMT>::kBias;
+    constexpr int emin = 1 - bias;
+    constexpr int top = ScaleFmt<FMT>::kMaxCode >> 3;                   // last binade; its position 7 is not a number
+
+    uint32_t eref[NBLK], lo_k[NBLK], hi_k[NBLK];
+    prune_window<B, FMT>(v, eref, lo_k, hi_k);
+    int d_lo = 0, d_hi = 0, b_lo = top, b_hi = 1;                       // relative / absolute binade ranges
+    bool sub = false;
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        d_lo = min(d_lo, (int)(lo_k[k] >> 3) - (int)eref[k]);
+        d_hi = max(d_hi, (int)(hi_k[k] >> 3) - (int)eref[k]);
+        b_lo = min(b_lo, max((int)(lo_k[k] >> 3), 1));
+        b_hi = max(b_hi, (int)(hi_k[k] >> 3));
+        sub |= lo_k[k] < 8u;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        d_lo = min(d_lo, __shfl_xor(d_lo, off, 64));
+        d_hi = max(d_hi, __shfl_xor(d_hi, off, 64));
+        b_lo = min(b_lo, __shfl_xor(b_lo, off, 64));
+        b_hi = max(b_hi, __shfl_xor(b_hi, off, 64));
+    }
+    d_lo = __builtin_amdgcn_readfirstlane(d_lo);
+    d_hi = __builtin_amdgcn_readfirstlane(d_hi);
+    b_lo = __builtin_amdgcn_readfirstlane(b_lo);
+    b_hi = __builtin_amdgcn_readfirstlane(b_hi);
+    const bool any_sub = __builtin_amdgcn_ballot_w64(sub) != 0ull;
+    const bool relative = (d_hi - d_lo) < (b_hi - b_lo);                // uniform
+
+    float w[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[0][j] = v[j];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[i][j] = quot(v[j], Recip{mant_rhi(i), mant_rlo(i)});
+    }
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = 1u; }
+
+    if (any_sub) {                                                      // uniform: codes 1 .. 7
+        const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
+        const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
+        const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
+        GroupArgMin<B> g;
+        g.begin();
+        try_candidate<B, 0, 0>(v, w[0], s1, g);
+        try_candidate<B, 0, 1>(v, w[0], s2, g);
+        try_candidate<B, 4, 2>(v, w[4], s2, g);
+        try_candidate<B, 0, 3>(v, w[0], s4, g);
+        try_candidate<B, 2, 4>(v, w[2], s4, g);
+        try_candidate<B, 4, 5>(v, w[4], s4, g);
+        try_candidate<B, 6, 6>(v, w[6], s4, g);
+        g.end(st, 1u);
+    }
+
+    if (!relative) {                                                    // union of the absolute windows
+        for (int ef = b_lo; ef <= b_hi; ++ef) {
+            const float scale2 = u2f((uint32_t)(ef + 127 - bias) << 23);
+            try_binade<B, FMT>(v, w, scale2, (uint32_t)ef << 3, st);
+        }
+        d_hi = d_lo - 1;                                                // skips the relative scan
+    }
+    for (int d = d_lo; d <= d_hi; ++d) {                                // uniform
+        float scale2[NBLK];
+        uint32_t code0[NBLK];
+        bool ok[NBLK], last[NBLK];
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) {
+            const int ef = (int)eref[k] + d;                            // this block's binade in step d
+            ok[k] = ef >= 1 && ef <= top;
+            const int efc = min(max(ef, 1), top);
+            last[k] = efc == top;
+            scale2[k] = u2f((uint32_t)(efc + 127 - bias) << 23);
+            code0[k] = (uint32_t)efc << 3;
+        }
+        GroupArgMin<B> g;
+        g.begin();
+        try_binade_rel_from<B, 0>(v, w, scale2, g);
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) g.drop_last(k, last[k]);
+        g.end(st, code0, ok);
+    }
+
+    // codes of the winners
+    float y[8];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        const Recip r = make_recip(sf_decode<FMT>(st.best_code[k]));
+#pragma unroll
+        for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
+    }
+    packed = e2m1_pack8(y, 1.0f);
+}
+
+// The same over the 255 power-of-two scales (bytes 0x00 .. 0xFE): no quotient, the conversion
+// applies 2^k itself, for the candidates and for the winners' codes.
+template <int B>
+__device__ __forceinline__ void brute_search_pow2(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int EPB = (B < 8) ? B : 8;
 #pragma unroll
-    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = (FMT == kE8M0) ? 0u : 1u; }
-
-    if constexpr (FMT == kE8M0) {
-        static_assert(!PRUNE, "the pruned search covers the 8-bit floating-point scale formats only");
-        for (uint32_t code0 = 0u; code0 < 256u; code0 += 8u) {
-            GroupArgMin<B> g;
-            g.begin();
-            try_pow2_from<B, 0>(v, code0, g);
-            g.end(st, code0);
-        }
-        // codes of the winners: the conversion applies each block's own power of two
-#pragma unroll
-        for (int k = 0; k < NBLK; ++k) S_best[k] = pow2_scale(st.best_code[k]);
-        packed = e2m1_pack8_scales<EPB>(v, S_best);
-    } else {
-        constexpr int bias = ScaleFmt<FMT>::kBias;
-        constexpr int emin = 1 - bias;                                  // exponent of the first binade
-
-        uint32_t lo_w = 1u, hi_w = (uint32_t)ScaleFmt<FMT>::kMaxCode;
-        if constexpr (PRUNE) prune_window<B, FMT>(v, lo_w, hi_w);
-
-        float w[8][8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) w[0][j] = v[j];
-#pragma unroll
-        for (int i = 1; i < 8; ++i) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) w[i][j] = quot(v[j], Recip{mant_rhi(i), mant_rlo(i)});
-        }
-
-        // sub-normal codes 1..7 = j * 2^(emin-3): 1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4
-        const float s1 = u2f((uint32_t)(127 + emin - 3) << 23);
-        const float s2 = u2f((uint32_t)(127 + emin - 2) << 23);
-        const float s4 = u2f((uint32_t)(127 + emin - 1) << 23);
-        if (lo_w < 8u) {                                                // uniform
-            GroupArgMin<B> g;
-            g.begin();
-            try_candidate<B, 0, 0>(v, w[0], s1, g);
-            try_candidate<B, 0, 1>(v, w[0], s2, g);
-            try_candidate<B, 4, 2>(v, w[4], s2, g);
-            try_candidate<B, 0, 3>(v, w[0], s4, g);
-            try_candidate<B, 2, 4>(v, w[2], s4, g);
-            try_candidate<B, 4, 5>(v, w[4], s4, g);
-            try_candidate<B, 6, 6>(v, w[6], s4, g);
-            g.end(st, 1u);
-        }
-
-        // normal codes: exponent field ef = 1 .. kMaxCode >> 3, value (1 + mi/8) * 2^(ef - bias)
-        for (uint32_t ef = max(lo_w >> 3, 1u); ef <= (hi_w >> 3); ++ef) {
-            const float scale2 = u2f((ef + (uint32_t)(127 - bias)) << 23);
-            try_binade<B, FMT>(v, w, scale2, ef << 3, st);
-        }
-
-        // codes of the winners
-        float y[8];
-#pragma unroll
-        for (int k = 0; k < NBLK; ++k) {
-            S_best[k] = sf_decode<FMT>(st.best_code[k]);
-            const Recip r = make_recip(S_best[k]);
-#pragma unroll
-            for (int i = 0; i < EPB; ++i) y[k * EPB + i] = quot(v[k * EPB + i], r);
-        }
-        packed = e2m1_pack8(y, 1.0f);
+    for (int k = 0; k < NBLK; ++k) { st.best_sse[k] = __builtin_inff(); st.best_code[k] = 0u; }
+    for (uint32_t code0 = 0u; code0 < 256u; code0 += 8u) {
+        GroupArgMin<B> g;
+        g.begin();
+        try_pow2_from<B, 0>(v, code0, g);
+        g.end(st, code0);
     }
+    float S[NBLK];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) S[k] = pow2_scale(st.best_code[k]);
+    packed = e2m1_pack8_scales<EPB>(v, S);
+}
+
+// Scale value of a winner byte.
+template <int FMT>
+__device__ __forceinline__ float brute_scale_value(uint32_t code)
+{
+    if constexpr (FMT == kE8M0) return pow2_scale(code);
+    else return sf_decode<FMT>(code);
 }
 
 // Clipping-only part of the winners' block SSE (appendix figure "Clipping only MSE"): elements with
@@ -355,9 +531,16 @@ brute_kernel(const void* __restrict__ x, int64_t n_full, float T_arg,
         }
         uint32_t packed;
         BruteState<B> st;
-        float S_best[NBLK], clip[4];
-        brute_search<B, FMT, PRUNE>(v, packed, st, S_best);
-        if (clip_out) brute_clip_sse<B>(v, S_best, clip);               // uniform
+        if constexpr (FMT == kE8M0) brute_search_pow2<B>(v, packed, st);
+        else if constexpr (PRUNE) brute_search_pruned<B, FMT>(v, packed, st);
+        else brute_search<B, FMT, false>(v, packed, st);
+        float clip[4];
+        if (clip_out) {                                                 // uniform
+            float S_best[NBLK];
+#pragma unroll
+            for (int k = 0; k < NBLK; ++k) S_best[k] = brute_scale_value<FMT>(st.best_code[k]);
+            brute_clip_sse<B>(v, S_best, clip);
+        }
 
         if (chunk < n_full) {
             codes[chunk] = packed;
@@ -405,8 +588,11 @@ brute_tail_kernel(const void* __restrict__ x, int64_t first, int count, float T_
     }
     uint32_t packed;
     BruteState<B> st;
+    if constexpr (FMT == kE8M0) brute_search_pow2<B>(v, packed, st);
+    else if constexpr (PRUNE) brute_search_pruned<B, FMT>(v, packed, st);
+    else brute_search<B, FMT, false>(v, packed, st);
     float S_best[NBLK], clip[4];
-    brute_search<B, FMT, PRUNE>(v, packed, st, S_best);
+    for (int k = 0; k < NBLK; ++k) S_best[k] = brute_scale_value<FMT>(st.best_code[k]);
     brute_clip_sse<B>(v, S_best, clip);
     if (threadIdx.x != 0) return;
     for (int i = 0; i < count / 2; ++i) codes[first / 2 + i] = (uint8_t)(packed >> (8 * i));
