@@ -238,7 +238,7 @@ class Workload:
                       torch.empty(nb_max, dtype=torch.uint8, device=dev),
                       torch.empty(nb_max, dtype=torch.float32, device=dev),
                       torch.empty(nb_max, dtype=torch.float32, device=dev)) for _ in range(n_sets)]
-        self.amax = torch.zeros(n_sets + 1, dtype=torch.float32, device=dev)
+        self.amax = torch.zeros(n_sets, dtype=torch.float32, device=dev)
         self.t_buf = torch.ones(n_sets, dtype=torch.float32, device=dev)
         self.deq = None
         self.dq = None
@@ -308,15 +308,17 @@ def main():
         elif kind == "quant_clip":
             c, s, e, cl = wl.views(k, b)
             mxq.quantize(x, b, fmt, rec, codes_out=c, scales_out=s, sse_out=e, clip_sse_out=cl)
-        elif kind == "absmax":                    # running maximum, two words used alternately
-            mxq.tensor_absmax_acc(x, wl.amax[k:k + 1], clear_word=wl.amax[k + 1:k + 2])
+        elif kind == "absmax":                    # running maximum; every call clears the next call's word
+            k1 = (k + 1) % wl.n_sets
+            mxq.tensor_absmax_acc(x, wl.amax[k:k + 1], clear_word=wl.amax[k1:k1 + 1])
         elif kind == "absmax_2launch":
             mxq.tensor_absmax(x, out=wl.amax[k:k + 1])
         elif kind == "absmax_ws":
             mxq.tensor_absmax(x, out=wl.amax[k:k + 1], workspace=wl.ws)
         elif kind in ("two_pass_cold", "two_pass_warm"):
             c, s, e, _ = wl.views(k, b)
-            mxq.tensor_absmax_acc(x, wl.amax[k:k + 1], clear_word=wl.amax[k + 1:k + 2])
+            k1 = (k + 1) % wl.n_sets
+            mxq.tensor_absmax_acc(x, wl.amax[k:k + 1], clear_word=wl.amax[k1:k1 + 1])
             mxq.quantize_hier(x, b, fmt, rec, wl.amax[k:k + 1], tensor_scale_out=wl.t_buf[k:k + 1],
                               codes_out=c, scales_out=s, sse_out=e)
         elif kind == "dequant":
@@ -396,7 +398,7 @@ def main():
             return e0.elapsed_time(e1) / (reps * N_SETS)
 
         by = N_ELEM * 2
-        ms_read = timed(lambda k: mxq.tensor_absmax_acc(w2.xs[k], w2.amax[k:k + 1], clear_word=w2.amax[k + 1:k + 2]))
+        ms_read = timed(lambda k: launch(w2, "absmax", 0, 0, 0, False, k))
         ms_copy = timed(lambda k: w2.deq[k].copy_(w2.xs[(k + 3) % N_SETS]))
         ms_fill = timed(lambda k: w2.deq[k].fill_(1.0))
         ceilings = {"hbm_read_ceiling_gb_s": round(by / ms_read / 1e6, 1),
@@ -451,6 +453,7 @@ def main():
         if kind in ("dequant", "dequant_f32", "clip", "hist"):
             need_dq(wl)
         warm = kind == "two_pass_warm"
+        wl.amax.zero_()
         hmode = "device" if (hier and tag == "a3" and kind == "quant" and rec < BRUTE) else hier
         if hmode == "device":                     # the quantise pass alone needs a valid abs-max per set
             for k in range(wl.n_sets):
@@ -461,20 +464,30 @@ def main():
             launch(wl, kind, b, fmt, rec, hmode, k, warm)
         torch.cuda.synchronize()
         reps = 2 if rec in (BRUTE, BRUTE_PRUNED) and kind == "quant" else (20 if tag == "f1" else 4)
-        # short launches: replayed as one HIP graph so that the host's launch rate does not
-        # enter the figure
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=side):
-            for k in order:
-                launch(wl, kind, b, fmt, rec, hmode, k, warm)
-        g.replay()
-        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
+        if profiling:
+            # under rocprofv3: plain launches, so that every dispatch is traced and counted by itself
+            e0.record()
+            for _ in range(reps):
+                for k in order:
+                    launch(wl, kind, b, fmt, rec, hmode, k, warm)
+            e1.record()
+            torch.cuda.synchronize()
+        else:
+            # short launches: replayed as one HIP graph so that the host's launch rate does not
+            # enter the figure
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for k in order:
+                    launch(wl, kind, b, fmt, rec, hmode, k, warm)
             g.replay()
-        e1.record()
-        torch.cuda.synchronize()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            del g
         ms = e0.elapsed_time(e1) / (reps * wl.n_sets)
         row = {"name": name, "workload": tag, "ms": round(ms, 5), "gelem_s": round(wl.n / ms / 1e6, 1)}
         if rec in (BRUTE, BRUTE_PRUNED) and kind == "quant":
@@ -492,7 +505,6 @@ def main():
         if warm:
             row["note"] = "same tensor every time: the quantise pass finds its 67 MB input in the 256 MB Infinity Cache"
         extra.append(row)
-        del g
 
     # config 5: the 32-layer model sweep, first layers, one HIP graph per (recipe, block size)
     sweep_rows = []
