@@ -137,6 +137,8 @@ KERNEL_OF_PASS = {
     "absmax_e4m3_b16": "mxq::stream_kernel<0, 16, 1, false, 0, false>",
     "absmax_pz_e4m3_b16": "mxq::stream_kernel<0, 16, 1, false, 0, false>",
     "4over6_e4m3_b16": "mxq::stream_kernel<0, 16, 1, true, 0, false>",
+    "4over6_e4m3_b8": "mxq::stream_kernel<0, 8, 1, true, 0, false>",
+    "4over6_e4m3_b32": "mxq::stream_kernel<0, 32, 1, true, 0, false>",
     "4over6_e4m3_b64": "mxq::stream_kernel<0, 64, 1, true, 0, false>",
     "absmax_e4m3_b16_H": "mxq::stream_kernel<0, 16, 1, false, 1, false>",
     "4over6_e4m3_b16_H": "mxq::stream_kernel<0, 16, 1, true, 1, false>",
@@ -149,6 +151,7 @@ KERNEL_OF_PASS = {
 }
 PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "hbm_traffic_bf16_4096x14336.md")
 PROFILE_VALU = os.path.join(ROOT, "profiles", "valu_counters_bf16_4096x14336.md")
+PROFILE_WAIT = os.path.join(ROOT, "profiles", "lds_counters_bf16_4096x14336.md")
 
 
 def profile_rows(path):
@@ -170,20 +173,24 @@ def profile_rows(path):
 def recorded(pass_name):
     """Counter figures of that pass's kernel from the committed rocprofv3 summaries: HBM bytes per
     launch (FETCH_SIZE + WRITE_SIZE runs, scaled by a plain copy of known size), VALU instructions
-    per 8-element chunk and VALU-busy share.  They are RECORDED figures, not measured in this run;
-    the commit they were taken at is returned with them."""
+    per 8-element chunk, and the shares of resident wavefront time spent waiting for an issue slot
+    and waiting for data.  They are RECORDED figures, not measured in this run; the commit they were
+    taken at is returned with them."""
     kern = KERNEL_OF_PASS.get(pass_name)
-    out = {"traffic": None, "valu_per_chunk": None, "valu_busy_pct": None, "commit": None}
+    out = {"traffic": None, "valu_per_chunk": None, "wait_issue_pct": None, "wait_data_pct": None, "commit": None}
     if kern is None:
         return out
     t, c1 = profile_rows(PROFILE_TRAFFIC)
     v, c2 = profile_rows(PROFILE_VALU)
-    out["commit"] = c1 or c2
+    w, c3 = profile_rows(PROFILE_WAIT)
+    out["commit"] = c1 or c2 or c3
     if kern in t:
         out["traffic"] = round(float(t[kern][4]) * 1e6)
     if kern in v:
-        out["valu_per_chunk"] = float(v[kern][3])
-        out["valu_busy_pct"] = float(v[kern][5].rstrip(" %"))
+        out["valu_per_chunk"] = float(v[kern][2])
+    if kern in w:
+        out["wait_issue_pct"] = float(w[kern][4].rstrip(" %"))
+        out["wait_data_pct"] = float(w[kern][5].rstrip(" %"))
     return out
 
 
@@ -423,6 +430,11 @@ def main():
             floor_ms = r["valu_per_chunk"] * chunks * 64 / LANE_OPS_PEAK * 1e3
             row["valu_instr_per_chunk_recorded"] = r["valu_per_chunk"]
             row["valu_issue_floor_ms_at_2p4GHz"] = round(floor_ms, 5)
+            row["wait_issue_pct_recorded"] = r["wait_issue_pct"]
+            row["wait_data_pct_recorded"] = r["wait_data_pct"]
+            row["bound_statement"] = ("limited by vector issue, not by HBM: the recorded counters show more wavefront time "
+                                      "waiting for an issue slot than for data, and the vector instructions alone need "
+                                      "valu_issue_floor_ms at the nominal clock")
 
     kern = []
     if passes:
@@ -544,6 +556,7 @@ def main():
                  "traffic": rec_["traffic"], "avg_launch_ms": r["ms"],
                  "frac_of_unpacked_fma_peak": round(r["tflop_s"] / (FP32_VECTOR_PEAK_TFLOPS / 2), 4),
                  "valu_instr_per_chunk_recorded": rec_["valu_per_chunk"],
+                 "wait_issue_pct_recorded": rec_["wait_issue_pct"], "wait_data_pct_recorded": rec_["wait_data_pct"],
                  "bound_statement": "issue-bound: about 34 vector instructions per (8 elements x candidate) "
                                     "against 32 algorithmic ones, vector units never idle; 0.32 of the packed-FMA "
                                     "peak, which the instruction set available to this build (no packed fp32) caps at "
@@ -556,7 +569,7 @@ def main():
                  "unit": "GB/s", "frac": r["frac"], "traffic": rec_["traffic"], "avg_launch_ms": r["ms"]}
             if "frac_of_copy" in r:
                 d["frac_of_copy"] = r["frac_of_copy"]
-        d["traffic_is"] = "recorded: committed rocprofv3 FETCH_SIZE/WRITE_SIZE summary, not measured in this run"
+        d["traffic_is"] = "recorded: committed rocprofv3 summaries under profiles/, not measured in this run"
         d["recorded_at_commit"] = rec_["commit"]
         if extra_fields:
             d.update(extra_fields)
