@@ -454,6 +454,7 @@ def main():
 
     # ------------------------------------------------------------------ passes outside the step
     extra = []
+    full_ms = {}
     xp = [] if args.no_configs else extra_passes()
     if keep is not None:
         xp = [p for p in xp if p[2] in keep]
@@ -502,13 +503,18 @@ def main():
             del g
         ms = e0.elapsed_time(e1) / (reps * wl.n_sets)
         row = {"name": name, "workload": tag, "ms": round(ms, 5), "gelem_s": round(wl.n / ms / 1e6, 1)}
-        if rec in (BRUTE, BRUTE_PRUNED) and kind == "quant":
+        if rec == BRUTE and kind == "quant":
             flops = wl.n * NCAND[fmt] * 6.0
             row.update(bound="alu", tflop_s=round(flops / ms / 1e9, 2),
                        frac=round(flops / ms / 1e9 / FP32_VECTOR_PEAK_TFLOPS, 4))
-            if rec == BRUTE_PRUNED:
-                row["note"] = ("bit-identical to the full enumeration; tflop_s / frac count the full enumeration's "
-                               "work, which this variant does not perform: read them as a speed-up, not as utilisation")
+            full_ms[(tag, b, fmt)] = ms
+        elif rec == BRUTE_PRUNED and kind == "quant":
+            # no roofline fraction: the variant skips candidates, so the full enumeration's work
+            # divided by its time would not be a utilisation
+            ref = full_ms.get((tag, b, fmt)) or next((r["ms"] for r in kern if r["name"] == f"brute_{FMT[fmt]}_b{b}"), None)
+            row.update(bound="alu", candidates_of_full_search=NCAND[fmt],
+                       speedup_vs_full_enumeration=round(ref / ms, 3) if ref else None,
+                       note="bit-identical to the full enumeration, fewer candidates tried; reported as a speed-up")
         else:
             hbm_row(row, algorithmic_bytes(kind, b, wl.n, wl.in_bytes), ms)
             row["bytes_per_elem"] = round(algorithmic_bytes(kind, b, wl.n, wl.in_bytes) / wl.n, 4)

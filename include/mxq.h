@@ -50,7 +50,7 @@ typedef enum { MXQ_ELEM_E2M1 = 0 } mxq_elem_fmt;
  *   E4M3   OFP8 E4M3 with the sign bit unused (Background): bias 7, subnormals m*2^-9
  *          (eps = 2^-9, stated under Eq. 3), largest value 0x7E = 448, 0x7F = NaN (never
  *          written).
- *   UE5M3  unsigned, 5 exponent + 3 mantissa bits (Background, Section 3.2).  The paper
+ *   UE5M3  unsigned, 5 exponent + 3 mantissa bits (Background; Results, "Downstream LLM Perplexity").  The paper
  *          gives no encoding; this library uses bias 15, subnormals m*2^-17, largest value
  *          0xFE = 1.75*2^16, 0xFF = NaN (never written). */
 typedef enum { MXQ_SCALE_E8M0 = 0, MXQ_SCALE_E4M3 = 1, MXQ_SCALE_UE5M3 = 2 } mxq_scale_fmt;
@@ -150,7 +150,7 @@ MXQ_API int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int blo
 
 /*
  * mxq_dequantize -- x^_i = (q_i * S) * tensor_scale, rounded to nearest even into out_dtype
- * ("de-quantization simply multiplies by S", Section 2).
+ * (de-quantisation, Section 2, paragraph after Eq. 2).
  *
  *   codes, scales  device, layouts as written by mxq_quantize, 4-byte aligned
  *   x_out          device, rows*cols elements of out_dtype, 16-byte aligned

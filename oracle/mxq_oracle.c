@@ -332,7 +332,7 @@ int orc_quantize(const void* x, int x_dtype, int64_t rows, int64_t cols, int blo
     if (x_dtype != ORC_DT_BF16 && x_dtype != ORC_DT_F32) return -1;
     if (scale_fmt < 0 || scale_fmt > 2 || recipe < 0 || recipe > 4) return -1;
     /* Eq. 4 chooses between two roundings of amax / M, which the floor rule of Eq. 1 does not
-     * define; the brute-force search "over possible scaling factors" applies to the power-of-two
+     * define; the brute-force search over the values of the scale format applies to the power-of-two
      * format as it stands: all 255 bytes 0x00 .. 0xFE are finite positive values. */
     if (scale_fmt == ORC_SCALE_E8M0 && (recipe == ORC_4OVER6 || recipe == ORC_4OVER6_PZ)) return -1;
     if (!(tensor_scale > 0.0f) || isinf(tensor_scale)) return -1;
@@ -423,7 +423,7 @@ static uint16_t f32_to_bf16_rne(float f)
 }
 
 /* De-quantisation: x^_i = fl32(fl32(q_i * S) * T), rounded to nearest even into the output
- * type ("de-quantization simply multiplies by S"). */
+ * type (de-quantisation, Section 2, paragraph after Eq. 2). */
 int orc_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t cols,
                    int block, int scale_fmt, float tensor_scale, void* x_out, int out_dtype)
 {

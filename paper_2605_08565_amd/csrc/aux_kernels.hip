@@ -1,4 +1,4 @@
-// De-quantisation ("de-quantization simply multiplies by S", Section 2) and the tensor
+// De-quantisation (Section 2, paragraph after Eq. 2: the codes times the block scale) and the tensor
 // abs-max of hierarchical scaling (first stage of the two-stage process, Section 2).
 #include "mxq_device.hpp"
 #include "mxq_launch.hpp"

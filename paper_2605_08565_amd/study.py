@@ -1,4 +1,4 @@
-"""Numerical study of Section 3.1 on the GPU library: MSE against the standard deviation.
+"""The "Numerical Study" of the paper's Results section on the GPU library: MSE against the standard deviation.
 
 For every sigma of 151 evenly spaced points in [0.0005, 0.05] and every block size in
 {4, 8, 16, 32}, 50 000 blocks are drawn from N(0, sigma^2) (seeded) and quantised with E2M1

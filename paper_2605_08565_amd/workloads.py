@@ -5,7 +5,8 @@ with the shapes and value distributions of the workloads and casts them to the s
 Both the GPU library and the CPU oracle are fed the same bytes produced here.
 
 The tensors stand in for the paper's workloads: i.i.d. normal blocks of the numerical study
-(Section 3.1) and the MLP weights / activations of 7B-14B language models (Section 3.2),
+(Results, "Numerical Study") and the MLP weights / activations of 7B-14B language models
+(Results, "Downstream LLM Perplexity"),
 whose real weights and evaluation corpus are not available.  Weights are heavy-tailed
 (Student-t, 4 degrees of freedom, scale 0.02); activations are N(0,1) with 1 % outlier
 channels multiplied by 50.

@@ -1,4 +1,4 @@
-"""The paper's numerical study (Section 3.1) run through the GPU library: parity with the oracle
+"""The paper's numerical study (Results, "Numerical Study") run through the GPU library: parity with the oracle
 on a slice of it, and the qualitative findings of the MSE-vs-sigma figure on the full grid."""
 import numpy as np
 import pytest

@@ -131,7 +131,7 @@ def test_ue5m3_table_structure(oracle):
     assert oracle.scale_decode(f, 0x78) == 1.0
     e4 = np.array([oracle.scale_decode(oracle.SCALE_E4M3, c) for c in range(0x7F)])
     assert (got[:0x7F] * 2.0 ** 8 == e4).all()
-    # wider absolute range than E4M3 on both ends (Background / Section 3.2)
+    # wider absolute range than E4M3 on both ends (Background; Results, "Downstream LLM Perplexity")
     assert got[1] < e4[1] and got[0xFE] > e4[0x7E]
 
 

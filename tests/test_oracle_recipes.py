@@ -338,7 +338,7 @@ def test_tree_sum_order(oracle):
         assert se == pytest.approx(float((e.astype(np.float64) ** 2).sum()), rel=1e-12)
 
 
-# ---------------------------------------------------------------- numerical study (Section 3.1)
+# ---------------------------------------------------------------- numerical study (Results, "Numerical Study")
 
 def test_numerical_study_regions(oracle):
     """Qualitative findings of the MSE-vs-sigma figure on N(0, sigma^2) blocks."""
@@ -376,7 +376,7 @@ def test_4over6_moves_mass_from_bin_6_to_bin_4(oracle):
 
 
 def test_hierarchical_scale_and_ue5m3_are_interchangeable(oracle):
-    """Section 3.2, on MSE instead of perplexity: for small-magnitude tensors E4M3 alone loses
+    """Results, "Downstream LLM Perplexity", on MSE instead of perplexity: for small-magnitude tensors E4M3 alone loses
     accuracy (its scales sit in the coarse sub-normal range or underflow); a per-tensor scale or
     the wider UE5M3 range both repair it, to the same level; a per-tensor scale on top of UE5M3
     changes nothing; 4-over-6 helps on top of either."""
