@@ -95,6 +95,7 @@ def extra_passes():
     p.append(("w2", "hist", "histogram_b4", 4, E4M3, 0, False))
     # config 1 and its full-size fp32 counterpart
     p.append(("f1", "quant", "config1_f32_1024x4096_absmax_e4m3_b16", 16, E4M3, ABSMAX, False))
+    p.append(("f1", "quant_batch", "config1_f32_1024x4096_absmax_e4m3_b16_batched_x16", 16, E4M3, ABSMAX, False))
     for r in (ABSMAX, FOUR6):
         p.append(("f2", "quant", f"f32_4096x14336_{REC[r]}_e4m3_b16", 16, E4M3, r, False))
     p.append(("f2", "absmax", "f32_4096x14336_tensor_absmax", 0, 0, 0, False))
@@ -312,6 +313,9 @@ def main():
                                   codes_out=c, scales_out=s, sse_out=e)
             else:
                 mxq.quantize(x, b, fmt, rec, tensor_scale=wl.T if hier else 1.0, codes_out=c, scales_out=s, sse_out=e)
+        elif kind == "quant_batch":               # all buffer sets in one call (two launches of eight tensors)
+            if k == 0:
+                mxq.quantize_batch(wl.xs, b, fmt, rec, outs=[wl.views(j, b)[:3] for j in range(wl.n_sets)])
         elif kind == "quant_clip":
             c, s, e, cl = wl.views(k, b)
             mxq.quantize(x, b, fmt, rec, codes_out=c, scales_out=s, sse_out=e, clip_sse_out=cl)
@@ -519,7 +523,8 @@ def main():
             hbm_row(row, algorithmic_bytes(kind, b, wl.n, wl.in_bytes), ms)
             row["bytes_per_elem"] = round(algorithmic_bytes(kind, b, wl.n, wl.in_bytes) / wl.n, 4)
         if tag == "f1":
-            row["note"] = "21 MB per launch: bound by launch and ramp-up, not by HBM (reported, no roofline claim)"
+            row["note"] = ("21 MB per launch: bound by launch and ramp-up, not by HBM (reported, no roofline claim)" if kind == "quant"
+                           else "mxq_quantize_batch: sixteen such tensors in two launches; time per tensor")
         if warm:
             row["note"] = "same tensor every time: the quantise pass finds its 67 MB input in the 256 MB Infinity Cache"
         extra.append(row)

@@ -128,6 +128,31 @@ MXQ_API int mxq_quantize_clip(const void* x, int64_t rows, int64_t cols, int blo
                       int x_dtype, void* stream);
 
 /*
+ * mxq_quantize_batch -- mxq_quantize (streaming recipes, no per-tensor scale) on several tensors
+ * with as few launches as possible: up to 8 tensors share one grid.  Same outputs, bit for bit,
+ * as one mxq_quantize call per tensor.  For the many small matrices of a model (Results,
+ * "Downstream LLM Perplexity": the MLP weights of every layer), whose individual launches are
+ * shorter than a launch's start-up and drain.
+ *
+ *   tensors  HOST array of `count` descriptors (read during the call, not kept); the pointers
+ *            inside are device pointers with the alignment mxq_quantize asks for; sse_out may
+ *            be NULL per tensor; tensors with rows*cols == 0 are skipped
+ *   block, elem_fmt, scale_fmt, recipe, x_dtype   shared by all tensors
+ * Every tensor is validated before anything is launched.  Errors as for mxq_quantize, plus
+ * UNSUPPORTED for BRUTE / BRUTE_PRUNED (a search launch is never short) and for more than 2^40
+ * elements in one call.
+ */
+typedef struct mxq_tensor {
+    const void* x;          /* device, rows*cols elements, 16-byte aligned            */
+    int64_t rows, cols;
+    uint8_t* codes_out;     /* device, rows*cols/2 bytes, 4-byte aligned               */
+    uint8_t* scales_out;    /* device, rows*cols/block bytes, 4-byte aligned           */
+    float* sse_out;         /* device, rows*cols/block floats, 16-byte aligned, or NULL */
+} mxq_tensor;
+MXQ_API int mxq_quantize_batch(const mxq_tensor* tensors, int count, int block,
+                       int elem_fmt, int scale_fmt, int recipe, int x_dtype, void* stream);
+
+/*
  * mxq_quantize_hier -- hierarchical scaling without a round trip to the host (the two-stage
  * process of Section 2 as a dynamic activation tensor needs it): mxq_quantize with the
  * per-tensor scale derived on the device from the tensor abs-max that mxq_tensor_absmax left

@@ -89,6 +89,52 @@ int mxq_quantize_clip(const void* x, int64_t rows, int64_t cols, int block,
                            codes_out, scales_out, sse_out, clip_sse_out, x_dtype, stream);
 }
 
+int mxq_quantize_batch(const mxq_tensor* tensors, int count, int block,
+                       int elem_fmt, int scale_fmt, int recipe, int x_dtype, void* stream)
+{
+    if (count < 0 || (count > 0 && !tensors)) return MXQ_ERR_INVALID_ARG;
+    if (!valid_block(block)) return MXQ_ERR_INVALID_ARG;
+    if (elem_fmt != MXQ_ELEM_E2M1) return MXQ_ERR_INVALID_ARG;
+    if (scale_fmt < MXQ_SCALE_E8M0 || scale_fmt > MXQ_SCALE_UE5M3) return MXQ_ERR_INVALID_ARG;
+    if (recipe < MXQ_RECIPE_ABSMAX || recipe > MXQ_RECIPE_BRUTE_PRUNED) return MXQ_ERR_INVALID_ARG;
+    if (x_dtype != MXQ_DT_BF16 && x_dtype != MXQ_DT_F32) return MXQ_ERR_INVALID_ARG;
+    if (recipe >= MXQ_RECIPE_BRUTE) return MXQ_ERR_UNSUPPORTED;               // the search is never launch-bound
+    if (scale_fmt == MXQ_SCALE_E8M0 && recipe >= MXQ_RECIPE_4OVER6) return MXQ_ERR_UNSUPPORTED;
+    // every tensor is validated before anything is launched
+    int64_t total = 0;
+    for (int i = 0; i < count; ++i) {
+        const mxq_tensor& t = tensors[i];
+        if (t.rows < 0 || t.cols < 0 || t.cols % block != 0) return MXQ_ERR_INVALID_ARG;
+        if (t.rows > 0 && t.cols > INT64_MAX / t.rows) return MXQ_ERR_INVALID_ARG;
+        const int64_t n = t.rows * t.cols;
+        if (n == 0) continue;
+        if (n >= ((int64_t)1 << 40) || (total += n) >= ((int64_t)1 << 40)) return MXQ_ERR_UNSUPPORTED;   // 32-bit slice counters
+        if (!t.x || !t.codes_out || !t.scales_out) return MXQ_ERR_INVALID_ARG;
+        if (!aligned(t.x, 16) || !aligned(t.codes_out, 4) || !aligned(t.scales_out, 4) ||
+            (t.sse_out && !aligned(t.sse_out, 16)))
+            return MXQ_ERR_ALIGNMENT;
+    }
+    constexpr int kGroup = 64;
+    mxq::StreamArgs a[kGroup];
+    int m = 0;
+    for (int i = 0; i <= count; ++i) {
+        if (i < count) {
+            const mxq_tensor& t = tensors[i];
+            const int64_t n = t.rows * t.cols;
+            if (n == 0) continue;
+            mxq::StreamArgs& s = a[m++];
+            s.x = t.x; s.n = n; s.dtype = x_dtype; s.block = block; s.scale_fmt = scale_fmt; s.recipe = recipe;
+            s.T = 1.0f; s.absmax_dev = nullptr; s.t_out = nullptr; s.codes = t.codes_out; s.scales = t.scales_out;
+            s.sse = t.sse_out; s.clip = nullptr; s.stream = static_cast<hipStream_t>(stream);
+        }
+        if (m == kGroup || (i == count && m > 0)) {
+            if (mxq::launch_stream_batch(a, m, static_cast<hipStream_t>(stream)) != hipSuccess) return MXQ_ERR_HIP;
+            m = 0;
+        }
+    }
+    return MXQ_OK;
+}
+
 int mxq_quantize_hier(const void* x, int64_t rows, int64_t cols, int block,
                       int elem_fmt, int scale_fmt, int recipe,
                       const float* absmax, float* tensor_scale_out,

@@ -6,6 +6,7 @@
 namespace mxq {
 
 constexpr int kThreads = 256;          // 4 wavefronts per workgroup
+constexpr int kMaxBatch = 8;           // tensors per launch of the batched streaming kernel
 
 // Arguments of one quantise call after host validation; n = rows * cols (blocks never
 // straddle rows because cols % block == 0, so the tensor is a flat run of blocks).
@@ -45,6 +46,7 @@ inline int stream_grid(int64_t n_chunks)
 }
 
 hipError_t launch_stream(const StreamArgs& a);       // ABSMAX, ABSMAX_PZ, 4OVER6, 4OVER6_PZ
+hipError_t launch_stream_batch(const StreamArgs* t, int count, hipStream_t stream);   // the same, several tensors per launch
 hipError_t launch_brute(const StreamArgs& a);        // BRUTE
 hipError_t launch_dequant(const DequantArgs& a);
 hipError_t launch_clip_sse(const void* x, const uint8_t* scales, int64_t n, int dtype, int block,

@@ -26,7 +26,9 @@ __device__ __forceinline__ void absmax_codes(float amax, uint32_t floor_code, ui
     const float y4 = quarter_of(amax);
     if constexpr (FMT == kE4M3) {
         const float m = ScaleFmt<kE4M3>::kMaxValue;
-        const uint32_t both = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(y6, m), fminf(y4, m), 0, false);
+        int old;                                       // the conversion writes the low half; the high half is never read
+        asm volatile("" : "=v"(old));
+        const uint32_t both = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(fminf(y6, m), fminf(y4, m), old, false);
         c6 = max(both & 0xFFu, floor_code);
         c4 = FOUR6 ? max((both >> 8) & 0xFFu, floor_code) : 0u;
     } else {
@@ -424,6 +426,98 @@ stream_kernel(const void* __restrict__ x, uint32_t n_slices, uint32_t last_chunk
         store_slice<B>(out[i], s_prev + (uint32_t)i, sl, codes, scales, sse_out, CLIP ? clip_out : nullptr);
 }
 
+// ---------------------------------------------------------------------------------------
+// Several tensors in one launch.  A model's smaller matrices hold a few microseconds of work each,
+// less than the start-up and drain of a launch; here up to kMaxBatch tensors share one grid.  The
+// slices of all tensors form one index space (prefix sums in the kernel arguments); a workgroup
+// resolves every tile to its tensor with a handful of scalar compares and then runs the very same
+// pipeline step as the single-tensor kernel.  No per-tensor scale, no clipping output.
+// ---------------------------------------------------------------------------------------
+struct BatchArgs {
+    const void* x[kMaxBatch];
+    uint32_t* codes[kMaxBatch];
+    uint8_t* scales[kMaxBatch];
+    float* sse[kMaxBatch];
+    uint32_t first[kMaxBatch + 1];        // first global slice of tensor t; first[count] = total
+    uint32_t last[kMaxBatch];             // chunks in tensor t's last slice, 1 .. 256
+    uint32_t count;
+};
+
+struct TileRef {                          // one tile = one slice of one tensor
+    uint32_t t, s;                        // tensor, slice inside it
+    Slices sl;
+};
+
+__device__ __forceinline__ TileRef locate(const BatchArgs& a, uint32_t g)
+{
+    uint32_t t = 0u;
+#pragma unroll
+    for (int k = 1; k < kMaxBatch; ++k) t += ((uint32_t)k < a.count && g >= a.first[k]) ? 1u : 0u;
+    return TileRef{t, g - a.first[t], Slices{a.first[t + 1] - a.first[t], a.last[t]}};
+}
+
+template <int DT, int B, int FMT, bool FOUR6>
+__device__ __forceinline__ void batch_step(RawChunk<DT> (&cur)[kItems], RawChunk<DT> (&nxt)[kItems],
+                                           TileOut<B> (&out)[kItems], bool have_prev, TileRef prev,
+                                           bool have_next, TileRef next, const BatchArgs& a, bool pz,
+                                           const ScaleEntry* tab, u32x4* wave_lds)
+{
+    static_assert(kItems == 1, "one slice per tile");
+    float v[8];
+    __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0)
+    widen<DT>(cur[0], v, wave_lds);
+    __builtin_amdgcn_sched_barrier(0);
+    if (have_prev)                                                   // uniform
+        store_slice<B>(out[0], prev.s, prev.sl, a.codes[prev.t], a.scales[prev.t], a.sse[prev.t], nullptr);
+    if (have_next) load_tile<DT>(nxt, a.x[next.t], next.s, next.sl); // uniform
+    __builtin_amdgcn_sched_barrier(0);
+    process_chunk<B, FMT, FOUR6, kNoT, false>(v, 1.0f, 1.0f, kNoT, pz, tab, out[0].packed, out[0].code, out[0].sse,
+                                              out[0].clip);
+}
+
+// (Resolving the descriptors of a tile one pipeline step ahead, pointers included, was measured
+// and is slower: it keeps three sets of pointers alive in scalar registers.)
+template <int DT, int B, int FMT, bool FOUR6>
+__global__ void __launch_bounds__(kThreads)
+stream_batch_kernel(const BatchArgs a, int pz)
+{
+    __shared__ ScaleEntry tab[(FMT == kE8M0) ? 1 : 256];
+    __shared__ u32x4 xpose[(DT == kF32) ? 2 * kThreads : 1];
+    u32x4* wave_lds = xpose + ((DT == kF32) ? 2u * (threadIdx.x & ~63u) : 0u);
+
+    const uint32_t total = a.first[a.count];
+    const uint32_t stride = gridDim.x;
+    uint32_t g = blockIdx.x;
+    if (g >= total) return;                                          // whole workgroup
+
+    RawChunk<DT> bufA[kItems], bufB[kItems];
+    bufA[0] = RawChunk<DT>{};
+    bufB[0] = RawChunk<DT>{};
+    TileRef cur = locate(a, g), prev = cur, next = cur;
+    load_tile<DT>(bufA, a.x[cur.t], cur.s, cur.sl);
+    if constexpr (FMT != kE8M0) fill_scale_table<FMT>(tab);
+    TileOut<B> out[kItems];
+    bool have_prev = false;
+    while (true) {
+        bool have_next = g + stride < total;
+        if (have_next) next = locate(a, g + stride);
+        batch_step<DT, B, FMT, FOUR6>(bufA, bufB, out, have_prev, prev, have_next, next, a, pz != 0, tab, wave_lds);
+        have_prev = true;
+        prev = cur;
+        if (!have_next) break;
+        cur = next;
+        g += stride;
+        have_next = g + stride < total;
+        if (have_next) next = locate(a, g + stride);
+        batch_step<DT, B, FMT, FOUR6>(bufB, bufA, out, true, prev, have_next, next, a, pz != 0, tab, wave_lds);
+        prev = cur;
+        if (!have_next) break;
+        cur = next;
+        g += stride;
+    }
+    store_slice<B>(out[0], prev.s, prev.sl, a.codes[prev.t], a.scales[prev.t], a.sse[prev.t], nullptr);
+}
+
 // Ragged tail: when n is not a multiple of 8 (only possible for b = 2 or 4) the last
 // `count` < 8 elements are handled by lane 0 of one wavefront, reading and writing element-wise.
 template <int DT, int B, int FMT, bool FOUR6, int TMODE>
@@ -539,6 +633,87 @@ static hipError_t launch_dt(const StreamArgs& a)
         case 64: return launch_block<DT, 64>(a);
         default: return launch_block<DT, 128>(a);
     }
+}
+
+// ------------------------------------------------------------------------------ batch dispatch
+
+template <int DT, int B, int FMT, bool FOUR6>
+static hipError_t launch_batch_recipe(const StreamArgs* t, int count, int pz, hipStream_t stream)
+{
+    // complete chunks of up to kMaxBatch tensors per launch; ragged tails (b = 2, 4) one small launch each
+    for (int i0 = 0; i0 < count; i0 += kMaxBatch) {
+        BatchArgs a{};
+        uint32_t n_t = 0u;
+        uint64_t total = 0u;
+        for (int i = i0; i < count && i < i0 + kMaxBatch; ++i) {
+            const int64_t n_full = t[i].n / 8;
+            if (n_full == 0) continue;
+            const int64_t slices = (n_full + kThreads - 1) / kThreads;
+            a.x[n_t] = t[i].x;
+            a.codes[n_t] = reinterpret_cast<uint32_t*>(t[i].codes);
+            a.scales[n_t] = t[i].scales;
+            a.sse[n_t] = t[i].sse;
+            a.first[n_t] = (uint32_t)total;
+            a.last[n_t] = (uint32_t)(n_full - (slices - 1) * kThreads);
+            total += (uint64_t)slices;
+            ++n_t;
+        }
+        if (n_t > 0u) {
+            a.first[n_t] = (uint32_t)total;                      // the host has bounded the sum below 2^32
+            a.count = n_t;
+            const dim3 grid(stream_grid((int64_t)total * kThreads)), block(kThreads);
+            hipLaunchKernelGGL((stream_batch_kernel<DT, B, FMT, FOUR6>), grid, block, 0, stream, a, pz);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    if constexpr (B < 8) {
+        for (int i = 0; i < count; ++i) {
+            const int64_t n_full = t[i].n / 8;
+            const int cnt = (int)(t[i].n - n_full * 8);
+            if (cnt > 0)
+                hipLaunchKernelGGL((stream_tail_kernel<DT, B, FMT, FOUR6, kNoT>), dim3(1), dim3(64), 0, stream, t[i].x,
+                                   n_full * 8, cnt, 1.0f, pz, (const float*)nullptr, (float*)nullptr, t[i].codes,
+                                   t[i].scales, t[i].sse, (float*)nullptr);
+        }
+    }
+    return hipGetLastError();
+}
+
+template <int DT, int B>
+static hipError_t launch_batch_block(const StreamArgs* t, int count, hipStream_t stream)
+{
+    const int recipe = t[0].recipe;
+    const bool four6 = (recipe == 2 || recipe == 3);
+    const int pz = (recipe == 1 || recipe == 3) ? 1 : 0;
+    switch (t[0].scale_fmt) {
+        case kE8M0: return launch_batch_recipe<DT, B, kE8M0, false>(t, count, 0, stream);
+        case kE4M3: return four6 ? launch_batch_recipe<DT, B, kE4M3, true>(t, count, pz, stream)
+                                 : launch_batch_recipe<DT, B, kE4M3, false>(t, count, pz, stream);
+        default: return four6 ? launch_batch_recipe<DT, B, kUE5M3, true>(t, count, pz, stream)
+                              : launch_batch_recipe<DT, B, kUE5M3, false>(t, count, pz, stream);
+    }
+}
+
+template <int DT>
+static hipError_t launch_batch_dt(const StreamArgs* t, int count, hipStream_t stream)
+{
+    switch (t[0].block) {
+        case 2: return launch_batch_block<DT, 2>(t, count, stream);
+        case 4: return launch_batch_block<DT, 4>(t, count, stream);
+        case 8: return launch_batch_block<DT, 8>(t, count, stream);
+        case 16: return launch_batch_block<DT, 16>(t, count, stream);
+        case 32: return launch_batch_block<DT, 32>(t, count, stream);
+        case 64: return launch_batch_block<DT, 64>(t, count, stream);
+        default: return launch_batch_block<DT, 128>(t, count, stream);
+    }
+}
+
+// `t[0 .. count)`: validated tensors that share dtype, block, scale format and a streaming recipe.
+hipError_t launch_stream_batch(const StreamArgs* t, int count, hipStream_t stream)
+{
+    if (count <= 0) return hipSuccess;
+    return (t[0].dtype == kBF16) ? launch_batch_dt<kBF16>(t, count, stream) : launch_batch_dt<kF32>(t, count, stream);
 }
 
 hipError_t launch_stream(const StreamArgs& a)

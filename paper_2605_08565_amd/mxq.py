@@ -23,6 +23,12 @@ DT_BF16, DT_F32 = 0, 1
 _lib = None
 
 
+class _Tensor(ctypes.Structure):
+    """struct mxq_tensor of include/mxq.h"""
+    _fields_ = [("x", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("codes_out", ctypes.c_void_p), ("scales_out", ctypes.c_void_p), ("sse_out", ctypes.c_void_p)]
+
+
 class MxqError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -43,6 +49,8 @@ def lib() -> ctypes.CDLL:
     L.mxq_quantize.argtypes = [vp, i64, i64, i32, i32, i32, i32, f32, vp, vp, vp, i32, vp]
     L.mxq_quantize_clip.restype = i32
     L.mxq_quantize_clip.argtypes = [vp, i64, i64, i32, i32, i32, i32, f32, vp, vp, vp, vp, i32, vp]
+    L.mxq_quantize_batch.restype = i32
+    L.mxq_quantize_batch.argtypes = [ctypes.POINTER(_Tensor), i32, i32, i32, i32, i32, i32, vp]
     L.mxq_quantize_hier.restype = i32
     L.mxq_quantize_hier.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
     L.mxq_dequantize.restype = i32
@@ -143,6 +151,41 @@ def quantize(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, tensor_sc
                               sse_out.data_ptr() if sse_out is not None else None,
                               _dtype_code(x), _stream_ptr(stream)))
     return codes_out, scales_out, sse_out
+
+
+def quantize_batch(xs, block: int, scale_fmt: int, recipe: int, outs=None, want_sse: bool = True, stream=None,
+                   elem_fmt: int = ELEM_E2M1):
+    """mxq_quantize_batch: the 2-D contiguous CUDA tensors `xs` (one dtype) in as few launches as
+    possible.  `outs`: optional list of (codes, scales, sse-or-None) per tensor.  Returns that list."""
+    xs = list(xs)
+    if outs is None:
+        outs = []
+        for x in xs:
+            rows, cols = x.shape
+            nb = cols // block if block > 0 else 0
+            outs.append((torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device),
+                         torch.empty((rows, nb), dtype=torch.uint8, device=x.device),
+                         torch.empty((rows, nb), dtype=torch.float32, device=x.device) if want_sse else None))
+    if len(outs) != len(xs):
+        raise ValueError("one output triple per tensor")
+    arr = (_Tensor * max(len(xs), 1))()
+    dt = None
+    for i, (x, (c, s, e)) in enumerate(zip(xs, outs)):
+        if not x.is_cuda or x.dim() != 2 or not x.is_contiguous():
+            raise ValueError("every x must be a contiguous 2-D tensor on the GPU")
+        if dt is None:
+            dt = _dtype_code(x)
+        elif dt != _dtype_code(x):
+            raise TypeError("all tensors of a batch share one dtype")
+        rows, cols = x.shape
+        _need(c, rows * cols // 2, "codes_out", torch.uint8)
+        _need(s, _nblocks(rows, cols, block), "scales_out", torch.uint8)
+        if e is not None:
+            _need(e, 4 * _nblocks(rows, cols, block), "sse_out", torch.float32)
+        arr[i] = _Tensor(x.data_ptr(), rows, cols, c.data_ptr(), s.data_ptr(), e.data_ptr() if e is not None else None)
+    _check(lib().mxq_quantize_batch(arr, len(xs), block, elem_fmt, scale_fmt, recipe,
+                                    dt if dt is not None else DT_BF16, _stream_ptr(stream)))
+    return outs
 
 
 def quantize_hier(x: torch.Tensor, block: int, scale_fmt: int, recipe: int, absmax: torch.Tensor,

@@ -6,9 +6,9 @@ every block size, one layer resident on the GPU at a time.
 
 Recipes: power-of-two MX (E8M0 abs-max), E4M3 abs-max, E4M3 prevent-zero, E4M3 4-over-6,
 UE5M3 abs-max, E4M3 brute force; block sizes 2 ... 128.  For every (recipe, block size) the
-seven matrices of a layer are quantised back to back (436 MB of input between two touches of
-a matrix, so the 256 MB Infinity Cache does not help), as one HIP graph replay with one event
-pair around it.
+seven matrices of a layer are quantised in one batched launch (mxq_quantize_batch; the search:
+seven launches back to back), 436 MB of input between two touches of a matrix, so the 256 MB
+Infinity Cache does not help, as one HIP graph replay with one event pair around it.
 Reports GElem/s and the aggregate MSE per (recipe, block size).
 
 Weights come from ``workloads.layer_matrix`` (numpy Philox, drawn on the host one layer ahead of
@@ -61,7 +61,7 @@ def draw_layer(layer: int, mats) -> None:
 
 
 def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool = True,
-        generator: str = "numpy", layer_ids=None) -> dict:
+        generator: str = "numpy", layer_ids=None, batched: bool = True, replays: int = 4) -> dict:
     """The smallest matrices (k, v: 4 M elements) quantise in a few microseconds, less than one
     launch through Python costs, so the seven launches of a (recipe, block size) group are
     captured once into a HIP graph over resident buffers and replayed for every layer."""
@@ -77,12 +77,18 @@ def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool
             for name, (r, c) in LAYER_SHAPES.items()}
 
     def group(b, fmt, rec):
+        views = []
         for name, x in mats.items():
             r, c = x.shape
             co, so, eo = outs[name]
             nb = r * c // b
-            mxq.quantize(x, b, fmt, rec, codes_out=co.view(r, c // 2),
-                         scales_out=so[:nb].view(r, c // b), sse_out=eo[:nb].view(r, c // b))
+            views.append((co.view(r, c // 2), so[:nb].view(r, c // b), eo[:nb].view(r, c // b)))
+        if rec < mxq.RECIPE_BRUTE and batched:
+            # the seven matrices share one launch: k and v hold less work than a launch costs
+            mxq.quantize_batch(list(mats.values()), b, fmt, rec, outs=views)
+        else:
+            for x, (co, so, eo) in zip(mats.values(), views):
+                mxq.quantize(x, b, fmt, rec, codes_out=co, scales_out=so, sse_out=eo)
 
     acc = {(rn, b): {"ms": 0.0, "elements": 0, "sse": 0.0} for rn, _, _ in recipes for b in blocks}
     warm = torch.zeros((8, 256), dtype=torch.bfloat16, device=dev)
@@ -117,16 +123,21 @@ def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool
         torch.cuda.synchronize()
         for rn, fmt, rec in recipes:
             for b in blocks:
+                # several replays between one event pair: the latency of submitting a graph (several
+                # microseconds, as long as a small matrix takes) is paid once, not per layer pass;
+                # a layer's input is 436 MB, so a replay still finds nothing in the Infinity Cache
+                reps = 1 if rec >= mxq.RECIPE_BRUTE else replays
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                if use_graphs:
-                    graphs[(rn, b)].replay()
-                else:
-                    group(b, fmt, rec)
+                for _ in range(reps):
+                    if use_graphs:
+                        graphs[(rn, b)].replay()
+                    else:
+                        group(b, fmt, rec)
                 e1.record()
                 torch.cuda.synchronize()
                 a = acc[(rn, b)]
-                a["ms"] += e0.elapsed_time(e1)
+                a["ms"] += e0.elapsed_time(e1) / reps
                 for name, x in mats.items():
                     a["elements"] += x.numel()
                     a["sse"] += float(outs[name][2][: x.numel() // b].to(torch.float64).sum())
@@ -135,7 +146,7 @@ def run(layers: int = N_LAYERS, blocks=BLOCKS, recipes=RECIPES, use_graphs: bool
         rows.append({"recipe": rn, "block": b, "gelem_s": round(a["elements"] / a["ms"] / 1e6, 1),
                      "mse": a["sse"] / a["elements"], "elements": a["elements"], "ms": round(a["ms"], 3)})
     ahead.shutdown()
-    return {"layers": len(ids), "layer_ids": ids, "graphs": use_graphs, "generator": generator,
+    return {"layers": len(ids), "layer_ids": ids, "graphs": use_graphs, "generator": generator, "batched": batched,
             "parity_checked_bytes": generator == "numpy", "rows": rows}
 
 
@@ -144,10 +155,11 @@ def main() -> None:
     ap.add_argument("--layers", type=int, default=N_LAYERS)
     ap.add_argument("--out", default="")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from Python instead")
+    ap.add_argument("--unbatched", action="store_true", help="one launch per matrix instead of one per layer")
     ap.add_argument("--generator", choices=("numpy", "gpu"), default="numpy",
                     help="numpy: workloads.layer_matrix bytes (the parity-checked ones); gpu: torch draws on the device")
     args = ap.parse_args()
-    res = run(args.layers, use_graphs=not args.no_graphs, generator=args.generator)
+    res = run(args.layers, use_graphs=not args.no_graphs, generator=args.generator, batched=not args.unbatched)
     text = json.dumps(res)
     if args.out:
         with open(args.out, "w") as f:

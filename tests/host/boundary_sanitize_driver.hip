@@ -18,6 +18,7 @@ static mxq::StreamArgs g_last;
 namespace mxq {
 hipError_t launch_stream(const StreamArgs& a) { ++g_launches; g_last = a; return hipSuccess; }
 hipError_t launch_brute(const StreamArgs& a) { ++g_launches; g_last = a; return hipSuccess; }
+hipError_t launch_stream_batch(const StreamArgs* t, int count, hipStream_t) { ++g_launches; g_last = t[count - 1]; return hipSuccess; }
 hipError_t launch_dequant(const DequantArgs&) { ++g_launches; return hipSuccess; }
 hipError_t launch_clip_sse(const void*, const uint8_t*, int64_t, int, int, int, float, float*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_histogram(const uint8_t*, const uint8_t*, int64_t, int, unsigned long long*, unsigned long long*, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -84,6 +85,28 @@ int main()
     EXPECT(mxq_quantize(P, 0, 64, 16, 0, 1, 0, 1.0f, P, P, F, 0, nullptr), MXQ_OK, 0);
     EXPECT(mxq_quantize(nullptr, 0, 64, 16, 0, 1, 0, 1.0f, nullptr, nullptr, nullptr, 0, nullptr), MXQ_OK, 0);
     EXPECT(mxq_quantize(P, 3, 0, 16, 0, 1, 0, 1.0f, P, P, F, 0, nullptr), MXQ_OK, 0);
+
+    // ---- mxq_quantize_batch: one launcher call per group of up to 64 non-empty tensors
+    {
+        mxq_tensor t[70];
+        for (int i = 0; i < 70; ++i) t[i] = mxq_tensor{P, 2, 64, P, P, (i & 1) ? F : nullptr};
+        t[3].rows = 0;                                                       // skipped
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 1, 2, 0, nullptr), MXQ_OK, 2);
+        if (g_last.n != 128 || g_last.recipe != 2 || g_last.T != 1.0f) { ++g_bad; std::printf("batch arguments not forwarded\n"); }
+        EXPECT(mxq_quantize_batch(t, 5, 16, 0, 1, 0, 1, nullptr), MXQ_OK, 1);
+        EXPECT(mxq_quantize_batch(t, 0, 16, 0, 1, 0, 1, nullptr), MXQ_OK, 0);
+        EXPECT(mxq_quantize_batch(nullptr, 3, 16, 0, 1, 0, 1, nullptr), MXQ_ERR_INVALID_ARG, 0);
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 1, 4, 0, nullptr), MXQ_ERR_UNSUPPORTED, 0);
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 0, 3, 0, nullptr), MXQ_ERR_UNSUPPORTED, 0);
+        t[69].cols = 72;
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 1, 0, 0, nullptr), MXQ_ERR_INVALID_ARG, 0);
+        t[69].cols = 64; t[68].x = P + 4;
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 1, 0, 0, nullptr), MXQ_ERR_ALIGNMENT, 0);
+        t[68].x = nullptr;
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 1, 0, 0, nullptr), MXQ_ERR_INVALID_ARG, 0);
+        t[68].x = P; t[0].rows = (int64_t)1 << 28; t[0].cols = (int64_t)1 << 12;
+        EXPECT(mxq_quantize_batch(t, 70, 16, 0, 1, 0, 0, nullptr), MXQ_ERR_UNSUPPORTED, 0);
+    }
 
     // ---- mxq_quantize_hier
     EXPECT(mxq_quantize_hier(P, 4, 64, 16, 0, 1, 2, F, F, P, P, F, 0, nullptr), MXQ_OK, 1);

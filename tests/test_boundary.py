@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(mxq):
     names = declared_symbols()
-    assert names == sorted(["mxq_quantize", "mxq_quantize_clip", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc", "mxq_tensor_absmax_static",
+    assert names == sorted(["mxq_quantize", "mxq_quantize_batch", "mxq_quantize_clip", "mxq_quantize_hier", "mxq_dequantize", "mxq_dequantize_hier", "mxq_tensor_absmax", "mxq_tensor_absmax_ws", "mxq_tensor_absmax_acc", "mxq_tensor_absmax_static",
                             "mxq_tensor_absmax_workspace_size", "mxq_clip_sse",
                             "mxq_histogram",
                             "mxq_tensor_scale_from_absmax", "mxq_scale_decode",
@@ -95,6 +95,30 @@ def test_argument_validation_without_a_launch(mxq):
     assert qc(x=None) == mxq.ERR_INVALID_ARG and qc(block=3) == mxq.ERR_INVALID_ARG
     assert qc(clip=P + 4) == mxq.ERR_ALIGNMENT and qc(sse=P + 8) == mxq.ERR_ALIGNMENT
     assert qc(fmt=0, rec=2) == mxq.ERR_UNSUPPORTED and qc(rows=0) == mxq.OK
+
+    T_ = mxq._Tensor
+
+    def qb(tensors, block=16, elem=0, fmt=1, rec=0, dt=0):
+        arr = (T_ * max(len(tensors), 1))(*tensors)
+        return L.mxq_quantize_batch(arr, len(tensors), block, elem, fmt, rec, dt, None)
+
+    good = T_(P, 4, 64, P, P, P)
+    assert qb([]) == mxq.OK and L.mxq_quantize_batch(None, 0, 16, 0, 1, 0, 0, None) == mxq.OK
+    assert L.mxq_quantize_batch(None, 2, 16, 0, 1, 0, 0, None) == mxq.ERR_INVALID_ARG
+    assert L.mxq_quantize_batch(None, -1, 16, 0, 1, 0, 0, None) == mxq.ERR_INVALID_ARG
+    assert qb([good], block=3) == mxq.ERR_INVALID_ARG and qb([good], fmt=5) == mxq.ERR_INVALID_ARG
+    assert qb([good], rec=9) == mxq.ERR_INVALID_ARG and qb([good], dt=2) == mxq.ERR_INVALID_ARG
+    assert qb([good], rec=4) == mxq.ERR_UNSUPPORTED and qb([good], rec=5) == mxq.ERR_UNSUPPORTED
+    assert qb([good], fmt=0, rec=2) == mxq.ERR_UNSUPPORTED
+    # one bad tensor anywhere in the list refuses the whole call, before any launch
+    assert qb([good, T_(None, 4, 64, P, P, P)]) == mxq.ERR_INVALID_ARG
+    assert qb([good, T_(P, 4, 72, P, P, P)]) == mxq.ERR_INVALID_ARG
+    assert qb([good, T_(P, -4, 64, P, P, P)]) == mxq.ERR_INVALID_ARG
+    assert qb([good, T_(P, 4, 64, None, P, P)]) == mxq.ERR_INVALID_ARG
+    assert qb([good, T_(P + 2, 4, 64, P, P, P)]) == mxq.ERR_ALIGNMENT
+    assert qb([good, T_(P, 4, 64, P, P, P + 4)]) == mxq.ERR_ALIGNMENT
+    assert qb([good, T_(P, 1 << 28, 1 << 12, P, P, P)]) == mxq.ERR_UNSUPPORTED
+    assert qb([T_(None, 0, 64, None, None, None), T_(P, 5, 0, P, P, P)]) == mxq.OK        # only empty tensors
 
     def qh(x=P, rows=4, cols=64, block=16, elem=0, fmt=1, rec=0, amax=P, t_out=P, codes=P, scales=P, sse=P, dt=0):
         return L.mxq_quantize_hier(x, rows, cols, block, elem, fmt, rec, amax, t_out, codes, scales, sse, dt, None)

@@ -170,6 +170,53 @@ def test_config1_full(oracle, mxq):
     check(oracle, mxq, x, 16, 1, 0, tag="config1")
 
 
+# ------------------------------------------------------------------ several tensors per launch
+
+@pytest.mark.parametrize("block", BLOCKS)
+def test_quantize_batch(oracle, mxq, block):
+    """mxq_quantize_batch against the oracle run tensor by tensor: eleven tensors (two launches)
+    of very different sizes -- one chunk, ragged last slices, several tiles per workgroup, an empty
+    tensor, for b = 2 and 4 element counts that are not a multiple of 8 -- both dtypes, every
+    streaming recipe and scale format, and one tensor without an SSE output."""
+    rng = np.random.default_rng(900 + block)
+    m = 3 if block < 8 else 1
+    shapes = [(1, block * m), (37, 1152), (3, 128 * 5), (0, 256), (513, 2048), (2, 128), (64, 4096), (7, block * 3 * m),
+              (1, 128), (300, 384), (2100, 1024)]
+    for to_bits in (W.f32_to_bf16_bits, lambda a: a):
+        xs_np = [to_bits((rng.standard_normal(sh) * 10.0 ** rng.uniform(-3, 1)).astype(np.float32)) for sh in shapes]
+        xs = [mxq.from_bits(a) if a.size else torch.empty(a.shape, dtype=torch.bfloat16 if a.dtype == np.uint16 else torch.float32,
+                                                        device="cuda") for a in xs_np]
+        for fmt, rec in [(0, 0), (1, 0), (1, 1), (1, 2), (1, 3), (2, 0), (2, 2)]:
+            print(f"[parity] batch b={block} dtype={xs_np[0].dtype} fmt={FMT_NAMES[fmt]} recipe={REC_NAMES[rec]}", flush=True)
+            outs = mxq.quantize_batch(xs, block, fmt, rec)
+            torch.cuda.synchronize()
+            for a, (c, s_, e) in zip(xs_np, outs):
+                if a.size == 0:
+                    continue
+                oc, os_, oe = oracle.quantize(a, block, fmt, rec)
+                assert (c.cpu().numpy() == oc).all() and (s_.cpu().numpy() == os_).all(), a.shape
+                assert (e.cpu().numpy().view(np.uint32) == oe.view(np.uint32)).all(), a.shape
+        outs = mxq.quantize_batch(xs[:3], block, 1, 2, want_sse=False)
+        assert all(o[2] is None for o in outs)
+        oc, os_, _ = oracle.quantize(xs_np[1], block, 1, 2)
+        assert (outs[1][0].cpu().numpy() == oc).all() and (outs[1][1].cpu().numpy() == os_).all()
+    with pytest.raises(mxq.MxqError):
+        mxq.quantize_batch(xs[:2], block, 1, 4)
+
+
+def test_quantize_batch_one_layer_equals_single_calls(mxq):
+    """The seven matrices of a model layer in one launch: the same bytes as seven mxq_quantize
+    calls (which the layer tests compare with the oracle)."""
+    from paper_2605_08565_amd import sweep
+    layer = sweep.host_layer(3)
+    xs = [mxq.from_bits(a) for a in layer.values()]
+    for block, fmt, rec in [(16, 1, 0), (32, 0, 0), (4, 1, 2), (128, 2, 1), (2, 1, 3)]:
+        outs = mxq.quantize_batch(xs, block, fmt, rec)
+        for x, (c, s_, e) in zip(xs, outs):
+            c1, s1, e1 = mxq.quantize(x, block, fmt, rec)
+            assert torch.equal(c, c1) and torch.equal(s_, s1) and torch.equal(e.view(torch.int32), e1.view(torch.int32))
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_ragged_and_tiny_shapes(oracle, mxq):
