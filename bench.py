@@ -568,10 +568,12 @@ def main():
                  "frac_of_unpacked_fma_peak": round(r["tflop_s"] / (FP32_VECTOR_PEAK_TFLOPS / 2), 4),
                  "valu_instr_per_chunk_recorded": rec_["valu_per_chunk"],
                  "wait_issue_pct_recorded": rec_["wait_issue_pct"], "wait_data_pct_recorded": rec_["wait_data_pct"],
-                 "bound_statement": "issue-bound: about 34 vector instructions per (8 elements x candidate) "
-                                    "against 32 algorithmic ones, vector units never idle; 0.32 of the packed-FMA "
-                                    "peak, which the instruction set available to this build (no packed fp32) caps at "
-                                    "0.50 even for a pure-FMA stream",
+                 "bound_statement": "issue-bound: %s vector instructions per (8 elements x candidate) "
+                                    "against 32 algorithmic ones (recorded counter / 254 candidates); %.2f of the "
+                                    "packed-FMA peak, which the instruction set available to this build (no packed "
+                                    "fp32) caps at 0.50 even for a pure-FMA stream"
+                                    % ("%.1f" % (rec_["valu_per_chunk"] / 254.0) if rec_["valu_per_chunk"] else "about 35",
+                                       r["frac"]),
                  "note": "algorithmic work = 6 flops per (element x candidate): scale, round, residual "
                          "FMA, square + add; peak is the packed-FMA fp32 vector peak (packed fp32 is "
                          "not available to this build: the unpacked FMA peak is half of it)"}

@@ -118,7 +118,8 @@ hipError_t launch_clip_sse(const void* x, const uint8_t* scales, int64_t n, int 
 // popular a code is, and fall on the banks like any 64-lane access.
 //
 // Partial results meet in 64-bit atomics on the caller's arrays, which a small kernel clears
-// first; few, large workgroups keep the number of those atomics small.  The bytes before the
+// first; few, large workgroups keep the number of those atomics small.  The scale bytes are
+// counted first, so that those atomics are on their way while the codes are counted.  The bytes before the
 // first 16-byte boundary, those after the last complete vector and a ragged last dword are
 // counted serially by one thread.
 __global__ void hist_clear_kernel(unsigned long long* elem_hist, unsigned long long* scale_hist)
@@ -130,7 +131,7 @@ __global__ void hist_clear_kernel(unsigned long long* elem_hist, unsigned long l
 
 constexpr int kHistThreads = 1024;
 constexpr int kHistCopies = 64;
-constexpr int kHistMaxGrid = 256;
+constexpr int kHistMaxGrid = 256;      // more workgroups lose more in same-address atomics than they gain (measured)
 static_assert(kHistThreads == 4 * 256 && kHistCopies == 64, "the closing reduction maps four threads to a code");
 
 // cnt[k] += number of nibbles of the four dwords whose low three bits equal k
@@ -157,9 +158,6 @@ histogram_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ 
 {
     __shared__ uint32_t sh_scale[kHistCopies * 256];
     __shared__ uint32_t sh_elem[8];
-    for (uint32_t i = threadIdx.x; i < (uint32_t)(kHistCopies * 256); i += kHistThreads) sh_scale[i] = 0u;
-    if (threadIdx.x < 8) sh_elem[threadIdx.x] = 0u;
-    __syncthreads();
 
     const int64_t stride = (int64_t)gridDim.x * kHistThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kHistThreads + threadIdx.x;
@@ -169,29 +167,39 @@ histogram_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ 
     const int64_t c_head = min(code_bytes, (int64_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(codes) & 15u)) & 15u));
     const int64_t c_vec = (code_bytes - c_head) >> 4;
     const u32x4* cv = reinterpret_cast<const u32x4*>(codes + c_head);
-    uint32_t cnt[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    for (int64_t i = t0; i < c_vec; i += 4 * stride) {               // four loads in flight per lane
-        u32x4 r[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) r[u] = __builtin_nontemporal_load(cv + min(i + u * stride, c_vec - 1));
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (i + u * stride < c_vec) count_magnitudes(r[u], cnt);
-    }
-
     // scale bytes: the same split
     const int64_t s_head = min(n_blocks, (int64_t)((16u - (uint32_t)(reinterpret_cast<uintptr_t>(scales) & 15u)) & 15u));
     const int64_t s_vec = (n_blocks - s_head) >> 4;
     const u32x4* sv = reinterpret_cast<const u32x4*>(scales + s_head);
+
+    // The first loads of both arrays leave before the LDS is cleared, so that their latency
+    // covers the clearing and, for the codes, the whole scale phase.
+    u32x4 rs[2] = {}, rc[4] = {};
+    if (s_vec > 0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) rs[u] = __builtin_nontemporal_load(sv + min(t0 + u * stride, s_vec - 1));
+    }
+    if (c_vec > 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rc[u] = __builtin_nontemporal_load(cv + min(t0 + u * stride, c_vec - 1));
+    }
+
+    for (uint32_t i = threadIdx.x; i < (uint32_t)(kHistCopies * 256); i += kHistThreads) sh_scale[i] = 0u;
+    if (threadIdx.x < 8) sh_elem[threadIdx.x] = 0u;
+    __syncthreads();
+
+    // Scales first: their partial histogram reaches the caller's array while the codes, by far
+    // the larger array, are still being counted.
     uint32_t* mine = sh_scale + (threadIdx.x & (kHistCopies - 1));        // word of code c: mine[c * 64]
     for (int64_t i = t0; i < s_vec; i += 2 * stride) {               // two loads in flight per lane
-        u32x4 r[2];
+        if (i != t0) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) r[u] = __builtin_nontemporal_load(sv + min(i + u * stride, s_vec - 1));
+            for (int u = 0; u < 2; ++u) rs[u] = __builtin_nontemporal_load(sv + min(i + u * stride, s_vec - 1));
+        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (i + u * stride >= s_vec) continue;
-            const uint32_t d[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+            const uint32_t d[4] = {rs[u].x, rs[u].y, rs[u].z, rs[u].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 atomicAdd(&mine[(d[j] & 0xFFu) * kHistCopies], 1u);
@@ -201,39 +209,55 @@ histogram_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ 
             }
         }
     }
-
     if (t0 == 0) {                                                   // the few bytes outside the vectors
-        for (int64_t b = 0; b < code_bytes; ++b) {
-            if (b == c_head) b += c_vec << 4;
-            if (b >= code_bytes) break;
-            cnt[codes[b] & 7u] += 1u;
-            cnt[(codes[b] >> 4) & 7u] += 1u;
-        }
         for (int64_t b = 0; b < n_blocks; ++b) {
             if (b == s_head) b += s_vec << 4;
             if (b >= n_blocks) break;
             atomicAdd(&mine[(uint32_t)scales[b] * kHistCopies], 1u);
         }
     }
-
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        uint32_t c = cnt[k];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) c += (uint32_t)__shfl_xor((int)c, off, 64);
-        if ((threadIdx.x & 63) == 0 && c) atomicAdd(&sh_elem[k], c);
-    }
     __syncthreads();
-    if (threadIdx.x < 8 && sh_elem[threadIdx.x]) atomicAdd(&elem_hist[threadIdx.x], (unsigned long long)sh_elem[threadIdx.x]);
     {   // four threads per code, 16 copies each
         const uint32_t code = threadIdx.x >> 2, part = threadIdx.x & 3u;
         uint32_t c = 0u;
 #pragma unroll
         for (int r = 0; r < kHistCopies / 4; ++r) c += sh_scale[code * kHistCopies + part * (kHistCopies / 4) + r];
-        c += (uint32_t)__shfl_xor((int)c, 1, 64);
-        c += (uint32_t)__shfl_xor((int)c, 2, 64);
+        c += dpp_u<kDppXor1>(c);
+        c += dpp_u<kDppXor2>(c);
         if (part == 0u && c) atomicAdd(&scale_hist[code], (unsigned long long)c);
     }
+
+    uint32_t cnt[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    for (int64_t i = t0; i < c_vec; i += 4 * stride) {               // four loads in flight per lane
+        if (i != t0) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) rc[u] = __builtin_nontemporal_load(cv + min(i + u * stride, c_vec - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * stride < c_vec) count_magnitudes(rc[u], cnt);
+    }
+    if (t0 == 0) {
+        for (int64_t b = 0; b < code_bytes; ++b) {
+            if (b == c_head) b += c_vec << 4;
+            if (b >= code_bytes) break;
+            cnt[codes[b] & 7u] += 1u;
+            cnt[(codes[b] >> 4) & 7u] += 1u;
+        }
+    }
+
+    // the 16 lanes of a DPP row add up in registers; one lane per row adds into the LDS
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        uint32_t c = cnt[k];
+        c += dpp_u<kDppXor1>(c);
+        c += dpp_u<kDppXor2>(c);
+        c += dpp_u<kDppHalfMirror>(c);
+        c += dpp_u<kDppMirror>(c);
+        if ((threadIdx.x & 15) == 0 && c) atomicAdd(&sh_elem[k], c);
+    }
+    __syncthreads();
+    if (threadIdx.x < 8 && sh_elem[threadIdx.x]) atomicAdd(&elem_hist[threadIdx.x], (unsigned long long)sh_elem[threadIdx.x]);
 }
 
 hipError_t launch_histogram(const uint8_t* codes, const uint8_t* scales, int64_t n, int block,
