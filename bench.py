@@ -57,19 +57,26 @@ WORKLOADS = {
 
 def step_passes():
     """(kind, name, block, fmt, recipe, hierarchical) for every launch of one step."""
+    # Order: the HBM-bound passes first, then the issue-bound streaming passes, brute force last.
+    # For about a millisecond after the brute-force passes the chip runs vector-bound kernels
+    # some 20 % slower (measured with the step in both orders: the slow-down follows whichever
+    # passes come next, and HBM-bound passes do not notice it), so the passes that would feel it
+    # are kept away from the step boundary.
     p = []
     for b in (8, 16, 32, 64):
-        for r in (ABSMAX, ABSMAX_PZ, FOUR6):
+        for r in (ABSMAX, ABSMAX_PZ):
             p.append(("quant", f"{REC[r]}_e4m3_b{b}", b, E4M3, r, False))
-    p.append(("absmax", "tensor_absmax", 0, 0, 0, False))
-    p.append(("quant", "absmax_e4m3_b16_H", 16, E4M3, ABSMAX, True))
-    p.append(("quant", "4over6_e4m3_b16_H", 16, E4M3, FOUR6, True))
     p.append(("quant", "absmax_e8m0_b32", 32, E8M0, ABSMAX, False))
     p.append(("quant", "absmax_ue5m3_b16", 16, UE5M3, ABSMAX, False))
+    p.append(("dequant", "dequantize_e4m3_b16_bf16", 16, E4M3, 0, False))
+    p.append(("absmax", "tensor_absmax", 0, 0, 0, False))
+    p.append(("quant", "absmax_e4m3_b16_H", 16, E4M3, ABSMAX, True))
+    for b in (8, 16, 32, 64):
+        p.append(("quant", f"4over6_e4m3_b{b}", b, E4M3, FOUR6, False))
+    p.append(("quant", "4over6_e4m3_b16_H", 16, E4M3, FOUR6, True))
     for fmt in (E4M3, UE5M3):
         for b in (16, 4):
             p.append(("quant", f"brute_{FMT[fmt]}_b{b}", b, fmt, BRUTE, False))
-    p.append(("dequant", "dequantize_e4m3_b16_bf16", 16, E4M3, 0, False))
     return p
 
 
