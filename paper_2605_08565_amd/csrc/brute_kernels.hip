@@ -153,6 +153,12 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 // fewer candidates.  Two facts bound the useful codes of a block with abs-max `amax`:
 //   (hi) S >= 4*amax quantises every element to zero, so all such candidates share one SSE
 //        (sum of squares); the first of them has the lowest code, the others can only tie.
+//   (hi2) an element with |v| < S/4 quantises to zero and contributes fl(v^2) to the SSE, exactly;
+//        the others contribute >= +0, and an fp32 sum of non-negative terms does not fall when a
+//        term grows.  So the tree sum of fl(v_i^2) over the elements with |v_i| < S0/4 is a lower
+//        bound of the SSE of every scale S >= S0; it grows with S0, and once it exceeds U (below)
+//        every higher code loses.  On weights this ends the window two to three binades above
+//        the abs-max scale, where (hi) alone lets it run to five or six.
 //   (lo) while 6*S < amax the abs-max element saturates and alone contributes
 //        fl(fl(amax - 6S)^2); fp32 sums of non-negative terms never fall below a term, so that
 //        is a lower bound of the candidate's SSE.  Once it exceeds U, the SSE of a reference
@@ -213,6 +219,38 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&ere
     else if constexpr (B == 4) { U[0] = p0 + p1; U[1] = p2 + p3; }
     else U[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
 
+    // (hi2): first binade above the reference binade whose lowest scale S0 = 2^(ef - bias) already
+    // loses.  The threshold S0 / 4 is a power of two; the sum uses the tree of the block SSE with +0
+    // in place of the elements that are not certain to vanish.
+    constexpr int kMaxUp = 5;                                            // (hi) ends the window at five or six anyway
+    constexpr uint32_t kNone = 1u << 20;
+    uint32_t dz[NBLK];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) dz[k] = kNone;
+    float vsq[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vsq[j] = v[j] * v[j];
+#pragma unroll 1
+    for (int d = 1; d <= kMaxUp; ++d) {                                  // uniform
+        float thr[NBLK], zs[8], Z[4];
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k)
+            thr[k] = u2f(((cref[k] >> 3) + (uint32_t)(d + 127 - ScaleFmt<FMT>::kBias - 2)) << 23);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zs[j] = (__builtin_fabsf(v[j]) < thr[j / EPB]) ? vsq[j] : 0.0f;
+        const float z0 = zs[0] + zs[1], z1 = zs[2] + zs[3], z2 = zs[4] + zs[5], z3 = zs[6] + zs[7];
+        if constexpr (B == 2) { Z[0] = z0; Z[1] = z1; Z[2] = z2; Z[3] = z3; }
+        else if constexpr (B == 4) { Z[0] = z0 + z1; Z[1] = z2 + z3; }
+        else Z[0] = group_sum<B / 8>((z0 + z1) + (z2 + z3));
+        bool open = false;
+#pragma unroll
+        for (int k = 0; k < NBLK; ++k) {
+            if (dz[k] == kNone && Z[k] > U[k]) dz[k] = (uint32_t)d;
+            open |= dz[k] == kNone;
+        }
+        if (__builtin_amdgcn_ballot_w64(open) == 0ull) break;           // every block of the wavefront is settled
+    }
+
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
         uint32_t lo = 1u, hi = cref[k];                 // the bound at cref is <= U: not a loser
@@ -228,6 +266,7 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&ere
         }
         lo_k[k] = lo;
         hi_k[k] = ceil_code<FMT>(4.0f * amax[k]);
+        if (dz[k] != kNone) hi_k[k] = min(hi_k[k], (((cref[k] >> 3) + dz[k]) << 3) - 1u);
         eref[k] = cref[k] >> 3;
     }
 }
