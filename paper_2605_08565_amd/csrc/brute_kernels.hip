@@ -166,7 +166,7 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 //        the losers form a prefix of the code range, found by bisection.
 // Windows of different blocks sit at different places of the code range (wherever the block's
 // abs-max puts them) but have nearly the same width, about one binade below the abs-max scale to
-// five above.  So the scan is wave-uniform in RELATIVE terms: in step d every block tries the
+// two or three above ((hi) alone: five to six).  So the scan is wave-uniform in RELATIVE terms: in step d every block tries the
 // binade d above the binade of its own abs-max scale (the power of two handed to the conversion
 // instruction is a per-lane register, the mantissa stays uniform), d running over the union of
 // the relative windows.  A wavefront with 128 small blocks then visits hardly more candidates
@@ -251,18 +251,48 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&ere
         if (__builtin_amdgcn_ballot_w64(open) == 0ull) break;           // every block of the wavefront is settled
     }
 
+    // (lo) at the granularity the scan has anyway: the highest code of a binade saturates least, so
+    // a binade whose highest code loses is lost as a whole, with everything below it.  Nearly every
+    // block settles in the first or second binade below its reference; the bisection over the
+    // codes runs only if some block of the wavefront has not settled after three.
+    uint32_t lo_b[NBLK];
+    bool unsettled = false;
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+        const uint32_t er = cref[k] >> 3;
+        lo_b[k] = kNone;
+#pragma unroll
+        for (int t = 1; t <= 3; ++t) {
+            // highest code of binade er - t: 1.875 * 2^(er - t - bias); the sub-normal "binade" 0
+            // ends with 0.875 * 2^(1 - bias)
+            const int ef = (int)er - t;
+            const float top_scale = (ef >= 1) ? 1.875f * u2f((uint32_t)(ef + 127 - ScaleFmt<FMT>::kBias) << 23)
+                                              : 0.875f * u2f((uint32_t)(1 + 127 - ScaleFmt<FMT>::kBias) << 23);
+            const float lim = 6.0f * top_scale;
+            const float dd = amax[k] - lim;
+            const bool loser = ef < 0 || ((lim < amax[k]) && (dd * dd > U[k]));
+            if (lo_b[k] == kNone && loser) lo_b[k] = (uint32_t)max(ef + 1, 0) << 3;
+        }
+        unsettled |= lo_b[k] == kNone;
+    }
+    const bool bisect = __builtin_amdgcn_ballot_w64(unsettled) != 0ull;  // uniform
+
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
         uint32_t lo = 1u, hi = cref[k];                 // the bound at cref is <= U: not a loser
+        if (bisect) {
 #pragma unroll 1
-        for (int it = 0; it < 8; ++it) {
-            if (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                const float lim = 6.0f * sf_decode<FMT>(mid);
-                const float d = amax[k] - lim;
-                const bool loser = (lim < amax[k]) && (d * d > U[k]);
-                if (loser) lo = mid + 1u; else hi = mid;
+            for (int it = 0; it < 8; ++it) {
+                if (lo < hi) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    const float lim = 6.0f * sf_decode<FMT>(mid);
+                    const float d = amax[k] - lim;
+                    const bool loser = (lim < amax[k]) && (d * d > U[k]);
+                    if (loser) lo = mid + 1u; else hi = mid;
+                }
             }
+        } else {
+            lo = max(lo_b[k], 1u);
         }
         lo_k[k] = lo;
         hi_k[k] = ceil_code<FMT>(4.0f * amax[k]);
