@@ -166,17 +166,16 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 //        the losers form a prefix of the code range, found by bisection.
 // Windows of different blocks sit at different places of the code range (wherever the block's
 // abs-max puts them) but have nearly the same width, about one binade below the abs-max scale to
-// two or three above ((hi) alone: five to six).  So the scan is wave-uniform in RELATIVE terms: in step d every block tries the
-// binade d above the binade of its own abs-max scale (the power of two handed to the conversion
-// instruction is a per-lane register, the mantissa stays uniform), d running over the union of
-// the relative windows.  A wavefront with 128 small blocks then visits hardly more candidates
-// than one block alone would, where a scan of the union of the absolute windows degraded with
-// the number of blocks per wavefront.  Lanes whose step falls outside the format's code range
-// are masked out; the sub-normal codes are one uniform group in front.  Every block still
-// visits a superset of its own window, in ascending code order.  When the blocks of a wavefront
-// are alike (weights), the union of the absolute windows is no wider than the relative one and
-// its scan is a few percent cheaper (uniform scale operand), so each wavefront takes whichever
-// of the two scans has fewer steps.
+// two or three above ((hi) alone: five to six).  So the scan is wave-uniform in RELATIVE terms:
+// in step t every block tries the t-th binade of its OWN window (the power of two handed to the
+// conversion instruction is a per-lane register, the mantissa stays uniform), t running up to
+// the widest window of the wavefront.  A wavefront with 128 small blocks then visits hardly more
+// candidates than its widest block alone would, where a scan of the union of the absolute
+// windows degrades with the number of blocks per wavefront and with the spread of their
+// magnitudes.  Lanes whose window has ended are masked out; the sub-normal codes are one uniform
+// group in front.  Every block visits its own window in ascending code order.  (A second scan
+// over the union of the absolute windows, chosen per wavefront when it has no more steps, was
+// measured: at best 3 % faster on weights at b = 4, slower everywhere else.)
 // ---------------------------------------------------------------------------------------
 template <int FMT>
 __device__ __forceinline__ uint32_t ceil_code(float y)      // smallest code >= 1 with value >= y
@@ -186,11 +185,10 @@ __device__ __forceinline__ uint32_t ceil_code(float y)      // smallest code >= 
     return max(c, 1u);
 }
 
-// Per block of the lane: binade (exponent field) of the abs-max scale, and the window [lo, hi] of
-// codes that can win.
+// Per block of the lane: the window [lo, hi] of codes that can win.
 template <int B, int FMT>
-__device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&eref)[BruteState<B>::NBLK],
-                                             uint32_t (&lo_k)[BruteState<B>::NBLK], uint32_t (&hi_k)[BruteState<B>::NBLK])
+__device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_k)[BruteState<B>::NBLK],
+                                             uint32_t (&hi_k)[BruteState<B>::NBLK])
 {
     constexpr int NBLK = BruteState<B>::NBLK;
     constexpr int LANES = (B < 8) ? 1 : B / 8;
@@ -297,7 +295,6 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&ere
         lo_k[k] = lo;
         hi_k[k] = ceil_code<FMT>(4.0f * amax[k]);
         if (dz[k] != kNone) hi_k[k] = min(hi_k[k], (((cref[k] >> 3) + dz[k]) << 3) - 1u);
-        eref[k] = cref[k] >> 3;
     }
 }
 
@@ -415,7 +412,7 @@ __device__ __forceinline__ void brute_search(const float (&v)[8], uint32_t& pack
     packed = e2m1_pack8(y, 1.0f);
 }
 
-// Pruned search: the relative scan described above.
+// Pruned search: windows, then the relative scan described above.
 template <int B, int FMT>
 __device__ __forceinline__ void brute_search_pruned(const float (&v)[8], uint32_t& packed, BruteState<B>& st)
 {
@@ -425,31 +422,21 @@ __device__ __forceinline__ void brute_search_pruned(const float (&v)[8], uint32_
     constexpr int emin = 1 - bias;
     constexpr int top = ScaleFmt<FMT>::kMaxCode >> 3;                   // last binade; its position 7 is not a number
 
-    uint32_t eref[NBLK], lo_k[NBLK], hi_k[NBLK];
-    prune_window<B, FMT>(v, eref, lo_k, hi_k);
-    int d_lo = 0, d_hi = 0, b_lo = top, b_hi = 1;                       // relative / absolute binade ranges
+    uint32_t lo_k[NBLK], hi_k[NBLK];
+    prune_window<B, FMT>(v, lo_k, hi_k);
+    // Steps of the scan: every block starts at the first binade of its OWN window, so the
+    // wavefront needs as many steps as its widest window has binades.
+    int w_max = -1;
     bool sub = false;
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
-        d_lo = min(d_lo, (int)(lo_k[k] >> 3) - (int)eref[k]);
-        d_hi = max(d_hi, (int)(hi_k[k] >> 3) - (int)eref[k]);
-        b_lo = min(b_lo, max((int)(lo_k[k] >> 3), 1));
-        b_hi = max(b_hi, (int)(hi_k[k] >> 3));
+        w_max = max(w_max, (int)(hi_k[k] >> 3) - max((int)(lo_k[k] >> 3), 1));
         sub |= lo_k[k] < 8u;
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        d_lo = min(d_lo, __shfl_xor(d_lo, off, 64));
-        d_hi = max(d_hi, __shfl_xor(d_hi, off, 64));
-        b_lo = min(b_lo, __shfl_xor(b_lo, off, 64));
-        b_hi = max(b_hi, __shfl_xor(b_hi, off, 64));
-    }
-    d_lo = __builtin_amdgcn_readfirstlane(d_lo);
-    d_hi = __builtin_amdgcn_readfirstlane(d_hi);
-    b_lo = __builtin_amdgcn_readfirstlane(b_lo);
-    b_hi = __builtin_amdgcn_readfirstlane(b_hi);
+    for (int off = 32; off >= 1; off >>= 1) w_max = max(w_max, __shfl_xor(w_max, off, 64));
+    w_max = __builtin_amdgcn_readfirstlane(w_max);
     const bool any_sub = __builtin_amdgcn_ballot_w64(sub) != 0ull;
-    const bool relative = (d_hi - d_lo) < (b_hi - b_lo);                // uniform
 
     float w[8][8];
 #pragma unroll
@@ -478,22 +465,15 @@ __device__ __forceinline__ void brute_search_pruned(const float (&v)[8], uint32_
         g.end(st, 1u);
     }
 
-    if (!relative) {                                                    // union of the absolute windows
-        for (int ef = b_lo; ef <= b_hi; ++ef) {
-            const float scale2 = u2f((uint32_t)(ef + 127 - bias) << 23);
-            try_binade<B, FMT>(v, w, scale2, (uint32_t)ef << 3, st);
-        }
-        d_hi = d_lo - 1;                                                // skips the relative scan
-    }
-    for (int d = d_lo; d <= d_hi; ++d) {                                // uniform
+    for (int t = 0; t <= w_max; ++t) {                                  // uniform
         float scale2[NBLK];
         uint32_t code0[NBLK];
         bool ok[NBLK], last[NBLK];
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) {
-            const int ef = (int)eref[k] + d;                            // this block's binade in step d
-            ok[k] = ef >= 1 && ef <= top;
-            const int efc = min(max(ef, 1), top);
+            const int ef = max((int)(lo_k[k] >> 3), 1) + t;             // this block's binade in step t
+            ok[k] = ef <= (int)(hi_k[k] >> 3);
+            const int efc = min(ef, top);
             last[k] = efc == top;
             scale2[k] = u2f((uint32_t)(efc + 127 - bias) << 23);
             code0[k] = (uint32_t)efc << 3;
