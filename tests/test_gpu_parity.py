@@ -567,6 +567,28 @@ def test_config4_brute_full_size(oracle, mxq, fmt, block):
     assert all(torch.equal(a, b) for a, b in zip(out, pr))
 
 
+def test_pruned_search_equals_full_search_on_activations_full_size(oracle, mxq):
+    """The pruned search against the full enumeration on the whole 8192 x 4096 activation tensor
+    (outlier channels: blocks of very different magnitude share a wavefront, some blocks hold one
+    outlier and otherwise tiny values), with and without the per-tensor scale, both scale formats,
+    small and large blocks: identical bytes.  The full enumeration of the same tensor is checked
+    against the oracle on 256 whole rows."""
+    x_np = W.config3()
+    x = mxq.from_bits(x_np)
+    T = oracle.tensor_scale(oracle.tensor_absmax(x_np), 1)
+    rows = sample_rows(x_np.shape[0], 256, seed=45)
+    for fmt in (1, 2):
+        for block in (2, 4, 16, 64):
+            for t in ((1.0, T) if fmt == 1 else (1.0,)):
+                print(f"[parity] config3 pruned-vs-full fmt={FMT_NAMES[fmt]} b={block} T={t}", flush=True)
+                full = mxq.quantize(x, block, fmt, 4, tensor_scale=t)
+                pr = mxq.quantize(x, block, fmt, 5, tensor_scale=t)
+                torch.cuda.synchronize()
+                assert all(torch.equal(a, b) for a, b in zip(full, pr))
+                if block in (4, 16) and fmt == 1:
+                    check_rows(oracle, x_np, rows, full, block, fmt, 4, T=t)
+
+
 def test_brute_force_over_power_of_two_scales_full_size(oracle, mxq):
     """The search over all 255 power-of-two scales on the full 4096 x 14336 weights (b = 32, the
     MX block size): 1 024 whole rows against the oracle; on every block its SSE is at most that of
