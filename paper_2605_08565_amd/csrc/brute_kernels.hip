@@ -150,7 +150,7 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 
 // ---------------------------------------------------------------------------------------
 // Pruned search (recipe BRUTE_PRUNED): same result as the full enumeration, bit for bit,
-// fewer candidates.  Two facts bound the useful codes of a block with abs-max `amax`:
+// fewer candidates.  Three facts bound the useful codes of a block with abs-max `amax`:
 //   (hi) S >= 4*amax quantises every element to zero, so all such candidates share one SSE
 //        (sum of squares); the first of them has the lowest code, the others can only tie.
 //   (hi2) an element with |v| < S/4 quantises to zero and contributes fl(v^2) to the SSE, exactly;
@@ -163,7 +163,7 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 //        fl(fl(amax - 6S)^2); fp32 sums of non-negative terms never fall below a term, so that
 //        is a lower bound of the candidate's SSE.  Once it exceeds U, the SSE of a reference
 //        candidate (the abs-max scale), the candidate cannot win; the bound falls with S, so
-//        the losers form a prefix of the code range, found by bisection.
+//        the losers form a prefix of the code range (tested per binade, bisection as fall-back).
 // Windows of different blocks sit at different places of the code range (wherever the block's
 // abs-max puts them) but have nearly the same width, about one binade below the abs-max scale to
 // two or three above ((hi) alone: five to six).  So the scan is wave-uniform in RELATIVE terms:
