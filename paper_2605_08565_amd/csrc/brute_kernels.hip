@@ -229,7 +229,7 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_
 #pragma unroll
     for (int j = 0; j < 8; ++j) vsq[j] = v[j] * v[j];
 #pragma unroll 1
-    for (int d = 1; d <= kMaxUp; ++d) {                                  // uniform
+    for (int d = 2; d <= kMaxUp; ++d) {                                  // uniform; d = 1 settles too few blocks to shorten a wavefront's scan
         float thr[NBLK], zs[8], Z[4];
 #pragma unroll
         for (int k = 0; k < NBLK; ++k)
