@@ -283,6 +283,7 @@ def main():
                     help="profiling aid: run only the passes of one workload tag (w2, a3, f1, f2), so that every "
                          "kernel instantiation in the trace ran on one tensor shape")
     ap.add_argument("--sweep-layers", type=int, default=2, help="layers of the 32-layer model sweep (config 5) to time")
+    ap.add_argument("--no-study", action="store_true", help="skip the timed numerical study (20 launches on fp32 tensors)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of one matrix (known size) for counter calibration")
     args = ap.parse_args()
@@ -557,6 +558,26 @@ def main():
                     row["frac_of_copy"] = round(gbs / copy_gbs, 4)
             sweep_rows.append(row)
 
+    # the numerical study (MSE against sigma): 20 launches on fp32 tensors of 30 M to 242 M elements
+    study_rows = []
+    if not args.no_configs and not profiling and not args.no_study:
+        for w in list(wl_cache):
+            if w != "w2":
+                del wl_cache[w]
+        torch.cuda.empty_cache()
+        from paper_2605_08565_amd import study
+        for r in study.timed():
+            row = dict(r)
+            if r["recipe"] == "brute_force":
+                tf = r["gelem_s"] * 1e9 * 126 * 6.0 / 1e12
+                row.update(bound="alu", tflop_s=round(tf, 2), frac=round(tf / FP32_VECTOR_PEAK_TFLOPS, 4))
+            else:
+                gbs = r["gelem_s"] * (4 + 0.5 + 5.0 / r["block"])
+                row.update(bound="hbm", gb_s=round(gbs, 1), frac=round(gbs / HBM_PEAK_GBS, 4))
+                if copy_gbs:
+                    row["frac_of_copy"] = round(gbs / copy_gbs, 4)
+            study_rows.append(row)
+
     if args.calibrate_copy and w2 is not None:
         for k in range(N_SETS):
             w2.deq[k].copy_(w2.xs[k])                 # 117 440 512 bytes read + the same written
@@ -606,6 +627,9 @@ def main():
         "config4": {"rows_in": "kernels", "names": [r["name"] for r in kern if r["name"].startswith("brute_")]},
         "config5": {"layers": args.sweep_layers, "generator": "numpy (workloads.layer_matrix: the bytes the parity tests check)",
                     "rows": sweep_rows},
+        "numerical_study": {"what": "151 sigmas x 50 000 blocks per block size, fp32 N(0, sigma^2), E4M3 scales; one "
+                                    "launch per (recipe, block size), 512 MB flushed through the caches between launches",
+                            "rows": study_rows},
         "diagnostics_and_other_blocks": [r for r in extra if r["workload"] == "w2"],
     }
     out = {

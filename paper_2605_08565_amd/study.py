@@ -54,6 +54,41 @@ def run(n_sigmas: int = 151, blocks_per_sigma: int = 50000, scale_fmt: int = 1) 
     return out
 
 
+def timed(n_sigmas: int = 151, blocks_per_sigma: int = 50000, scale_fmt: int = 1, repeats: int = 3) -> list:
+    """The same 20 launches timed one by one with events on the launch stream (mean of `repeats`
+    launches after one warm-up): rows of {"recipe", "block", "elements", "ms", "gelem_s"}.  Between two timed launches a 512 MB fill
+    pushes the input out of the 256 MB Infinity Cache (the b = 4 tensor alone would fit)."""
+    import torch
+
+    from . import mxq
+
+    sig = study_sigmas(n_sigmas)
+    flush = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    rows = []
+    for b in BLOCKS:
+        x = mxq.from_bits(study_tensor(sig, blocks_per_sigma, b))
+        r, c = x.shape
+        codes = torch.empty((r, c // 2), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((r, c // b), dtype=torch.uint8, device="cuda")
+        sse = torch.empty((r, c // b), dtype=torch.float32, device="cuda")
+        for name, rec in RECIPES.items():
+            total = 0.0
+            for it in range(repeats + 1):                     # the first launch is a warm-up
+                flush.fill_(1)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                mxq.quantize(x, b, scale_fmt, rec, codes_out=codes, scales_out=scales, sse_out=sse)
+                e1.record()
+                e1.synchronize()
+                if it > 0:
+                    total += e0.elapsed_time(e1)
+            ms = total / repeats
+            rows.append({"recipe": name, "block": b, "elements": r * c, "ms": round(ms, 5),
+                         "gelem_s": round(r * c / ms / 1e6, 1)})
+        del x, codes, scales, sse
+    return rows
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="")
