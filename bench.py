@@ -93,6 +93,10 @@ def extra_passes():
         for b in (16, 4):
             p.append(("w2", "quant", f"brute_pruned_{FMT[fmt]}_b{b}", b, fmt, BRUTE_PRUNED, False))
     p.append(("w2", "quant", "brute_e8m0_b32", 32, E8M0, BRUTE, False))
+    # the wider scale format with 4-over-6 and with the per-tensor scale
+    p.append(("w2", "quant", "4over6_ue5m3_b16", 16, UE5M3, FOUR6, False))
+    p.append(("w2", "quant", "absmax_ue5m3_b16_H", 16, UE5M3, ABSMAX, True))
+    p.append(("w2", "quant", "4over6_ue5m3_b16_H", 16, UE5M3, FOUR6, True))
     p.append(("w2", "dequant_f32", "dequantize_e4m3_b16_f32", 16, E4M3, 0, False))
     p.append(("w2", "absmax_2launch", "tensor_absmax_two_launches", 0, 0, 0, False))
     p.append(("w2", "absmax_ws", "tensor_absmax_workspace", 0, 0, 0, False))
@@ -262,6 +266,7 @@ class Workload:
         self.sh = torch.empty(256, dtype=torch.int64, device=dev)
         A = float(mxq.tensor_absmax(x0).cpu()[0])
         self.T = mxq.tensor_scale_from_absmax(A, E4M3)
+        self.T_by_fmt = {E4M3: self.T, UE5M3: mxq.tensor_scale_from_absmax(A, UE5M3), E8M0: 1.0}
 
     def views(self, k, b):
         c, s, e, cl = self.outs[k]
@@ -320,7 +325,8 @@ def main():
                 mxq.quantize_hier(x, b, fmt, rec, wl.amax[k:k + 1], tensor_scale_out=wl.t_buf[k:k + 1],
                                   codes_out=c, scales_out=s, sse_out=e)
             else:
-                mxq.quantize(x, b, fmt, rec, tensor_scale=wl.T if hier else 1.0, codes_out=c, scales_out=s, sse_out=e)
+                mxq.quantize(x, b, fmt, rec, tensor_scale=wl.T_by_fmt[fmt] if hier else 1.0, codes_out=c, scales_out=s,
+                             sse_out=e)
         elif kind == "quant_batch":               # all buffer sets in one call (two launches of eight tensors)
             if k == 0:
                 mxq.quantize_batch(wl.xs, b, fmt, rec, outs=[wl.views(j, b)[:3] for j in range(wl.n_sets)])
