@@ -589,6 +589,27 @@ def test_pruned_search_equals_full_search_on_activations_full_size(oracle, mxq):
                     check_rows(oracle, x_np, rows, full, block, fmt, 4, T=t)
 
 
+def test_binade_shift_invariance_full_size(mxq):
+    """A property that holds at any size, on the full 4096 x 14336 weights in the launch
+    configuration the benchmark times: multiplying the inputs by 4 (exact in bf16) leaves every
+    element code as it is, moves every UE5M3 scale byte up by two binades (16 codes) and multiplies
+    every block SSE by 16 exactly -- for all streaming recipes, the full search and the pruned one."""
+    x = mxq.from_bits(W.config2())
+    x4 = x * 4
+    for block in (4, 16):
+        for rec in (0, 1, 2, 3, 4, 5):
+            print(f"[parity] shift invariance b={block} recipe={REC_NAMES[rec]}", flush=True)
+            c0, s0, e0 = mxq.quantize(x, block, 2, rec)
+            c1, s1, e1 = mxq.quantize(x4, block, 2, rec)
+            torch.cuda.synchronize()
+            normal = s0 >= 16                                    # a binade of margin above the sub-normal codes
+            assert float(normal.float().mean()) > 0.99
+            assert torch.equal(s1[normal].to(torch.int32), s0[normal].to(torch.int32) + 16)
+            assert torch.equal(e1[normal], e0[normal] * 16)
+            keep = normal.repeat_interleave(block // 2, dim=1)
+            assert torch.equal(c1[keep], c0[keep])
+
+
 def test_brute_force_over_power_of_two_scales_full_size(oracle, mxq):
     """The search over all 255 power-of-two scales on the full 4096 x 14336 weights (b = 32, the
     MX block size): 1 024 whole rows against the oracle; on every block its SSE is at most that of
