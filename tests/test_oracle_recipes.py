@@ -422,3 +422,19 @@ def test_binade_shift_invariance(oracle, block):
                 assert (ck[okc] == c0[okc]).all(), (fmt, rec, k)
                 assert (sk.astype(np.int64)[ok] == s0.astype(np.int64)[ok] + step * k).all(), (fmt, rec, k)
                 assert (ek[ok] == (e0 * np.float32(4.0 ** k))[ok]).all(), (fmt, rec, k)
+
+
+def test_sign_symmetry(oracle):
+    """Negating the inputs flips the sign bit of every element code (bit 3 of each nibble, zeros
+    included: the sign is copied from the input) and changes nothing else: the abs-max, every
+    scale, every residual magnitude and every SSE depend on magnitudes only."""
+    x = W.student_t_weights(32, 256, seed=78)
+    xf = W.bf16_bits_to_f32(x)
+    neg = W.f32_to_bf16_bits(-xf)
+    for fmt in (oracle.SCALE_E8M0, oracle.SCALE_E4M3, oracle.SCALE_UE5M3):
+        for rec in ((0, 1, 4) if fmt == oracle.SCALE_E8M0 else (0, 1, 2, 3, 4)):
+            for block in (2, 16, 128):
+                c0, s0, e0 = oracle.quantize(x, block, fmt, rec)
+                c1, s1, e1 = oracle.quantize(neg, block, fmt, rec)
+                assert (c1 == (c0 ^ 0x88)).all() and (s1 == s0).all()
+                assert (e1.view(np.uint32) == e0.view(np.uint32)).all()
