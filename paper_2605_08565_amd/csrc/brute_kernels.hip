@@ -150,20 +150,17 @@ __device__ __forceinline__ void try_binade(const float (&v)[8], const float (&w)
 
 // ---------------------------------------------------------------------------------------
 // Pruned search (recipe BRUTE_PRUNED): same result as the full enumeration, bit for bit,
-// fewer candidates.  Four facts bound the useful codes of a block with abs-max `amax`:
+// fewer candidates.  Three facts bound the useful codes of a block with abs-max `amax`:
 //   (hi) S >= 4*amax quantises every element to zero, so all such candidates share one SSE
 //        (sum of squares); the first of them has the lowest code, the others can only tie.
-//   (hi2) an element with |v| < S/4 quantises to zero and contributes fl(v^2) to the SSE, exactly;
-//        the others contribute >= +0, and an fp32 sum of non-negative terms does not fall when a
-//        term grows.  So the tree sum of fl(v_i^2) over the elements with |v_i| < S0/4 is a lower
-//        bound of the SSE of every scale S >= S0; it grows with S0, and once it exceeds U (below)
-//        every higher code loses.  On weights this ends the window two to three binades above
-//        the abs-max scale, where (hi) alone lets it run to five or six.
-//   (hi3) once S0 / 2 > amax, every element quantises to 0 or to S/2 under any S >= S0, with a
-//        residual of |v| or S/2 - |v| >= S0/2 - |v| > 0; so fl(min(v^2, (S0/2 - |v|)^2)) may stand
-//        in (hi2) for the elements that are not certain to vanish.  It settles the blocks whose
-//        elements are all of similar magnitude, which (hi2) leaves to (hi); tested in the fourth
-//        and fifth binade above the reference only, where S0 / 2 > amax can hold.
+//   (hi2) under any scale S >= S0 an element with |v| < S0/2 quantises to 0 or to S/2, with a
+//        residual of |v| or of S/2 - |v| >= S0/2 - |v| > 0, so its square in the SSE is at least
+//        min(fl(v^2), fl(fl(S0/2 - |v|)^2)) (for |v| < S0/4, where it is certain to vanish, that is
+//        fl(v^2) itself); the other elements contribute >= +0, and an fp32 sum of non-negative
+//        terms does not fall when a term grows.  The tree sum of these terms is therefore a lower
+//        bound of the SSE of every scale >= S0; it grows with S0, and once it exceeds U (below)
+//        every higher code loses.  On weights this ends the window two binades above the abs-max
+//        scale, where (hi) alone lets it run to five or six.
 //   (lo) while 6*S < amax the abs-max element saturates and alone contributes
 //        fl(fl(amax - 6S)^2); fp32 sums of non-negative terms never fall below a term, so that
 //        is a lower bound of the candidate's SSE.  Once it exceeds U, the SSE of a reference
@@ -223,8 +220,7 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_
     else U[0] = group_sum<B / 8>((p0 + p1) + (p2 + p3));
 
     // (hi2): first binade above the reference binade whose lowest scale S0 = 2^(ef - bias) already
-    // loses.  The threshold S0 / 4 is a power of two; the sum uses the tree of the block SSE with +0
-    // in place of the elements that are not certain to vanish.
+    // loses.  thr = S0 / 4; the sum uses the tree of the block SSE.
     constexpr int kMaxUp = 5;                                            // (hi) ends the window at five or six anyway
     constexpr uint32_t kNone = 1u << 20;
     uint32_t dz[NBLK];
@@ -240,15 +236,10 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_
         for (int k = 0; k < NBLK; ++k)
             thr[k] = u2f(((cref[k] >> 3) + (uint32_t)(d + 127 - ScaleFmt<FMT>::kBias - 2)) << 23);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) zs[j] = (__builtin_fabsf(v[j]) < thr[j / EPB]) ? vsq[j] : 0.0f;
-        if (d >= 4) {                                                    // uniform: (hi3), S0 / 2 = 2 * thr
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float half = 2.0f * thr[j / EPB];
-                const float gap = half - __builtin_fabsf(v[j]);
-                const float alt = fminf(vsq[j], gap * gap);
-                if (half > amax[j / EPB] && !(__builtin_fabsf(v[j]) < thr[j / EPB])) zs[j] = alt;
-            }
+        for (int j = 0; j < 8; ++j) {
+            const float half = 2.0f * thr[j / EPB];                      // S0 / 2
+            const float gap = half - __builtin_fabsf(v[j]);
+            zs[j] = (gap > 0.0f) ? fminf(vsq[j], gap * gap) : 0.0f;     // |v| < S0/4: the minimum is v^2
         }
         const float z0 = zs[0] + zs[1], z1 = zs[2] + zs[3], z2 = zs[4] + zs[5], z3 = zs[6] + zs[7];
         if constexpr (B == 2) { Z[0] = z0; Z[1] = z1; Z[2] = z2; Z[3] = z3; }

@@ -5,11 +5,9 @@ The search over all scale codes (Section 2, "brute-force" baseline of the Numeri
 a code only if that code cannot be the lowest-code minimiser.  With U the SSE under the abs-max
 scale code c_ref (Eq. 2, at least code 1):
 
-  upper side  for a power of two S0, the tree sum of fl(v_i^2) over the elements with
-              |v_i| < S0 / 4 is a lower bound of the SSE under every scale >= S0 (such elements
-              quantise to zero and keep their whole square; the rest add >= 0); once S0 / 2 > amax
-              the rest add at least min(fl(v_i^2), fl(fl(S0/2 - |v_i|)^2)) (they quantise to 0 or
-              to S/2);
+  upper side  for a power of two S0, the tree sum of min(fl(v_i^2), fl(fl(S0/2 - |v_i|)^2)) over the
+              elements with |v_i| < S0 / 2 is a lower bound of the SSE under every scale >= S0
+              (such elements quantise to 0 or to S/2; the rest add >= 0);
   lower side  while 6 S < amax, fl(fl(amax - 6 S)^2) is a lower bound of the SSE under S.
 
 A bound that exceeds U rules the code out.  The kernels apply both per binade of the scale
@@ -68,12 +66,8 @@ def test_window_bounds_hold_for_every_code(oracle, fmt, b, kind):
         for d in range(2, 6):
             ef = eref + d
             s0 = np.float32(2.0 ** (ef - bias))
-            terms = np.where(np.abs(v) < np.float32(0.25) * s0, vsq, np.float32(0))
-            half = np.float32(0.5) * s0
-            if d >= 4 and half > amax:                   # every element quantises to 0 or S/2 from here on
-                gap = (half - np.abs(v)).astype(np.float32)
-                alt = np.minimum(vsq, (gap * gap).astype(np.float32))
-                terms = np.where(np.abs(v) < np.float32(0.25) * s0, vsq, alt)
+            gap = (np.float32(0.5) * s0 - np.abs(v)).astype(np.float32)
+            terms = np.where(gap > 0, np.minimum(vsq, (gap * gap).astype(np.float32)), np.float32(0))
             bound = tree_sum32(terms)
             above = np.nonzero(scale >= float(s0))[0]
             assert np.all(sse[above] >= bound), (kind, b, fmt, d)
