@@ -230,7 +230,9 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_
 #pragma unroll
     for (int j = 0; j < 8; ++j) vsq[j] = v[j] * v[j];
 #pragma unroll 1
-    for (int d = 2; d <= kMaxUp; ++d) {                                  // uniform; d = 1 settles too few blocks to shorten a wavefront's scan
+    // uniform.  Only the widest window of a wavefront costs steps: with 32 blocks per wavefront it
+    // ends two or three binades up, with 128 or more (b <= 4) four or five, so the tests start there.
+    for (int d = (B <= 4) ? 4 : 2; d <= kMaxUp; ++d) {
         float thr[NBLK], zs[8], Z[4];
 #pragma unroll
         for (int k = 0; k < NBLK; ++k)
