@@ -229,10 +229,15 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_
     float vsq[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) vsq[j] = v[j] * v[j];
+    // Only the widest window of a wavefront costs steps, so the search is for the first binade d at
+    // which EVERY block of the wavefront loses (a block is given the lowest tested d at which it
+    // loses: never too low).  With 32 blocks per wavefront that is two or three binades up and the
+    // tests simply ascend from 2; with 128 or more (b <= 4) it is usually four or five, so d = 4 is
+    // probed first, then 5 if some block survives it, else 3 and 2 as long as all blocks lose.
+    int d = (B <= 4) ? 4 : 2;
+    bool descending = false;
 #pragma unroll 1
-    // uniform.  Only the widest window of a wavefront costs steps: with 32 blocks per wavefront it
-    // ends two or three binades up, with 128 or more (b <= 4) four or five, so the tests start there.
-    for (int d = (B <= 4) ? 4 : 2; d <= kMaxUp; ++d) {
+    for (int it = 0; it < 4; ++it) {                                     // uniform
         float thr[NBLK], zs[8], Z[4];
 #pragma unroll
         for (int k = 0; k < NBLK; ++k)
@@ -247,13 +252,21 @@ __device__ __forceinline__ void prune_window(const float (&v)[8], uint32_t (&lo_
         if constexpr (B == 2) { Z[0] = z0; Z[1] = z1; Z[2] = z2; Z[3] = z3; }
         else if constexpr (B == 4) { Z[0] = z0 + z1; Z[1] = z2 + z3; }
         else Z[0] = group_sum<B / 8>((z0 + z1) + (z2 + z3));
-        bool open = false;
+        bool survives = false;
 #pragma unroll
         for (int k = 0; k < NBLK; ++k) {
-            if (dz[k] == kNone && Z[k] > U[k]) dz[k] = (uint32_t)d;
-            open |= dz[k] == kNone;
+            if (Z[k] > U[k]) dz[k] = min(dz[k], (uint32_t)d);
+            else survives = true;
         }
-        if (__builtin_amdgcn_ballot_w64(open) == 0ull) break;           // every block of the wavefront is settled
+        const bool all_lose = __builtin_amdgcn_ballot_w64(survives) == 0ull;
+        if constexpr (B <= 4) {
+            if (it == 0) descending = all_lose;
+            if (descending) { if (!all_lose || d == 2) break; --d; }
+            else { if (all_lose || d == kMaxUp) break; ++d; }
+        } else {
+            if (all_lose || d == kMaxUp) break;
+            ++d;
+        }
     }
 
     // (lo) at the granularity the scan has anyway: the highest code of a binade saturates least, so
